@@ -113,7 +113,11 @@ BlockClass classify(const float* x, int len, float eb, int e_eb) {
   int m = e_v - e_eb;
   if (m < 0) m = 0;
   if (m > 23) m = 23;
-  if (e_eb < e_M - 21 || m >= 16 || e_v >= 127) return r;  // RAW
+  // RAW when the bound lies below 4 ulp of the largest magnitude, when 16 or more mantissa bits would be
+  // kept (4 bytes per element anyway), or when a value lies in the top binade: there the rounded centred
+  // value plus the median can reach 2^128 and decode as Inf, which would break the bound of Sec. III-B
+  // (e.g. {0, FLT_MAX} under a bound of 2^120).  Below the top binade |x| + abs_eb < 2^128 - 2^103.
+  if (e_eb < e_M - 21 || m >= 16 || e_M >= 127) return r;  // RAW
   r.type = T_NONCONST; r.mu = mu; r.m = m; r.reqlen = 9 + m;
   return r;
 }

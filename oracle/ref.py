@@ -35,31 +35,70 @@ def build(force: bool = False) -> str:
     return _SO
 
 
+def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
+    c_sz, c_vp, c_f = ctypes.c_size_t, ctypes.c_void_p, ctypes.c_float
+    L.ccoll_ref_max_compressed_bytes.restype = c_sz
+    L.ccoll_ref_max_compressed_bytes.argtypes = [c_sz]
+    L.ccoll_ref_compress_stats.restype = ctypes.c_int
+    L.ccoll_ref_compress_stats.argtypes = [c_vp, c_sz, c_f, c_vp, c_sz, ctypes.POINTER(c_sz), c_vp]
+    L.ccoll_ref_compress.restype = ctypes.c_int
+    L.ccoll_ref_compress.argtypes = [c_vp, c_sz, c_f, c_vp, c_sz, ctypes.POINTER(c_sz)]
+    L.ccoll_ref_decompress.restype = ctypes.c_int
+    L.ccoll_ref_decompress.argtypes = [c_vp, c_sz, c_vp, c_sz]
+    L.ccoll_ref_decompress_range.restype = ctypes.c_int
+    L.ccoll_ref_decompress_range.argtypes = [c_vp, c_sz, c_sz, c_sz, c_vp]
+    L.ccoll_ref_reduce_step_op.restype = ctypes.c_int
+    L.ccoll_ref_reduce_step_op.argtypes = [ctypes.c_int, c_vp, c_sz, c_vp, c_sz, c_f, c_vp, c_sz, ctypes.POINTER(c_sz)]
+    L.ccoll_ref_reduce_step.restype = ctypes.c_int
+    L.ccoll_ref_reduce_step.argtypes = [c_vp, c_sz, c_vp, c_sz, c_f, c_vp, c_sz, ctypes.POINTER(c_sz)]
+    L.ccoll_ref_classify_block.restype = ctypes.c_int
+    L.ccoll_ref_classify_block.argtypes = [c_vp, ctypes.c_int, c_f, ctypes.POINTER(ctypes.c_int),
+                                           ctypes.POINTER(c_f), ctypes.POINTER(ctypes.c_int)]
+    return L
+
+
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
         build()
-        L = ctypes.CDLL(_SO)
-        c_sz, c_vp, c_f = ctypes.c_size_t, ctypes.c_void_p, ctypes.c_float
-        L.ccoll_ref_max_compressed_bytes.restype = c_sz
-        L.ccoll_ref_max_compressed_bytes.argtypes = [c_sz]
-        L.ccoll_ref_compress_stats.restype = ctypes.c_int
-        L.ccoll_ref_compress_stats.argtypes = [c_vp, c_sz, c_f, c_vp, c_sz, ctypes.POINTER(c_sz), c_vp]
-        L.ccoll_ref_compress.restype = ctypes.c_int
-        L.ccoll_ref_compress.argtypes = [c_vp, c_sz, c_f, c_vp, c_sz, ctypes.POINTER(c_sz)]
-        L.ccoll_ref_decompress.restype = ctypes.c_int
-        L.ccoll_ref_decompress.argtypes = [c_vp, c_sz, c_vp, c_sz]
-        L.ccoll_ref_decompress_range.restype = ctypes.c_int
-        L.ccoll_ref_decompress_range.argtypes = [c_vp, c_sz, c_sz, c_sz, c_vp]
-        L.ccoll_ref_reduce_step_op.restype = ctypes.c_int
-        L.ccoll_ref_reduce_step_op.argtypes = [ctypes.c_int, c_vp, c_sz, c_vp, c_sz, c_f, c_vp, c_sz, ctypes.POINTER(c_sz)]
-        L.ccoll_ref_reduce_step.restype = ctypes.c_int
-        L.ccoll_ref_reduce_step.argtypes = [c_vp, c_sz, c_vp, c_sz, c_f, c_vp, c_sz, ctypes.POINTER(c_sz)]
-        L.ccoll_ref_classify_block.restype = ctypes.c_int
-        L.ccoll_ref_classify_block.argtypes = [c_vp, ctypes.c_int, c_f, ctypes.POINTER(ctypes.c_int),
-                                               ctypes.POINTER(c_f), ctypes.POINTER(ctypes.c_int)]
-        _lib = L
+        _lib = _declare(ctypes.CDLL(_SO))
     return _lib
+
+
+def build_variant(edits, out_dir: str) -> ctypes.CDLL:
+    """Mutation testing of the pins: compiles a copy of the oracle source with the given (old, new) text
+    replacements, each of which must match exactly once, and returns the loaded library."""
+    text = open(_SRC).read()
+    for old, new in edits:
+        if text.count(old) != 1:
+            raise ValueError(f"edit does not match exactly once: {old!r}")
+        text = text.replace(old, new)
+    tag = "%08x" % (hash(tuple(edits)) & 0xffffffff)
+    src = os.path.join(out_dir, f"ccoll_szx_ref_{tag}.cpp")
+    so = os.path.join(out_dir, f"libccoll_szx_ref_{tag}.so")
+    with open(src, "w") as f:
+        f.write(text)
+    subprocess.run(["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC", src, "-o", so],
+                   check=True)
+    return _declare(ctypes.CDLL(so))
+
+
+class use_library:
+    """Context manager: the module's functions call library L inside the block (the pins run against a variant)."""
+
+    def __init__(self, L: ctypes.CDLL):
+        self.L = L
+
+    def __enter__(self):
+        global _lib
+        lib()
+        self.saved, _lib = _lib, self.L
+        return self.L
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self.saved
+        return False
 
 
 class RefError(RuntimeError):

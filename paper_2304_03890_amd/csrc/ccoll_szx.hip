@@ -273,7 +273,9 @@ __device__ __forceinline__ RowClass classify_row(const u32 (&xb)[kE], float eb, 
   const u32 amax = max(mxb & 0x7fffffffu, mnb & 0x7fffffffu);
   const int e_M = (int)max(amax >> 23, 1u) - 127;
   int m = e_v - e_eb; m = m < 0 ? 0 : (m > 23 ? 23 : m);
-  if (e_eb < e_M - 21 || m >= 16 || e_v >= 127) { rc.mu = 0.0f; return rc; }
+  // raw: bound below 4 ulp of the largest magnitude, 16 or more mantissa bits to keep, or a value in the top
+  // binade (the rounded centred value plus the median could reach 2^128 and decode as Inf)
+  if (e_eb < e_M - 21 || m >= 16 || e_M >= 127) { rc.mu = 0.0f; return rc; }
   rc.type = 1; rc.m = (u32)m;
   return rc;
 }

@@ -61,6 +61,26 @@ def test_adversarial_blocks(ctx, eb):
     check_roundtrip(ctx, x[37:1500], eb, f"adversarial shifted eb={eb}")
 
 
+def test_bit_budget_edges(ctx):
+    """The hand-derived edge blocks of the RAW guard, the 16-bit budget, the top binade and the denormal
+    exponent (tests/test_oracle_bit_budget.py), alone and packed into one input: bytes and floats equal the oracle's."""
+    import sys, os
+    sys.path.insert(0, os.path.dirname(__file__))
+    from test_oracle_bit_budget import edge_cases, narrow_blocks
+    for name, x, eb, _, _ in edge_cases():
+        check_roundtrip(ctx, x, eb, name)
+        full = np.resize(x, 128 * 3 + 7).astype(np.float32)      # the same values as whole blocks with a ragged tail
+        check_roundtrip(ctx, full, eb, name + " (tiled)")
+    rng = np.random.default_rng(17)
+    for i, (x, eb) in enumerate(narrow_blocks(rng, 200)):
+        check_roundtrip(ctx, np.resize(x, 128 * 2 + 3).astype(np.float32), eb, f"narrow {i}")
+    # values next to FLT_MAX under huge bounds (blocks with a value in the top binade are stored raw)
+    fmax = float(np.finfo(np.float32).max)
+    for k in range(40):
+        x = (fmax * 2.0 ** -(k % 3) * (1 - rng.uniform(0, 1, 128 * 5 + 9) * 2.0 ** -int(rng.integers(1, 20)))).astype(np.float32)
+        check_roundtrip(ctx, x, np.float32(2.0 ** rng.uniform(100, 127)), f"float-max {k}")
+
+
 def test_raw_bits(ctx):
     rng = np.random.default_rng(3)
     bits = rng.integers(0, 2 ** 32, 128 * 45 + 5, dtype=np.uint64).astype(np.uint32)
