@@ -138,6 +138,23 @@ int ccoll_reduce_step_op_async(ccoll_ctx *ctx, int op, const float *d_local, siz
                                size_t cin_bytes, float abs_eb, void *d_cout, size_t cout_cap,
                                unsigned long long *d_result);
 
+/* For callers that cannot allocate device memory or hold a context: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The same decompression as ccoll_szx_decompress_async, with
+ * no context: what the context would hold for the call (its result and error words and the chunk-start
+ * offsets derived from the front index, 8 bytes per chunk) lives in a static device array inside the library,
+ * about 210 KB, which every device that runs the library keeps until the process ends.  The call allocates
+ * and frees nothing and only enqueues kernels (no memset, no copy) on hip_stream (a hipStream_t, NULL = the
+ * default stream) of `device`.
+ *   n <= CCOLL_STATIC_MAX_ELEMS, else CCOLL_EINVAL (use a context for larger streams).
+ *   d_result: device, 8-byte aligned, two 64-bit words, required: receives {0, status as a signed 64-bit value}
+ *   when the work completes (CCOLL_OK, or CCOLL_ECORRUPT for a malformed or truncated stream).
+ * All calls on one device share that device's array: calls that overlap in time on one device (two streams,
+ * two threads) race and give undefined results; calls that follow each other on one stream are fine.  The
+ * first call on a device resolves the array's address (hipGetSymbolAddress): make it outside a capture. */
+#define CCOLL_STATIC_MAX_ELEMS 134217728   /* 2^27 */
+int ccoll_szx_decompress_static(int device, void *hip_stream, const void *d_in, size_t in_bytes,
+                                float *d_out, size_t n, unsigned long long *d_result);
+
 /* Waits for the context's stream and returns the status of the last *_async call that used
  * the context's own result slot; *bytes (may be NULL) receives its byte count. */
 int ccoll_wait(ccoll_ctx *ctx, size_t *bytes);

@@ -54,6 +54,8 @@ _SIGNATURES = {
     "ccoll_reduce_step_async": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                                ctypes.c_size_t, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t,
                                                ctypes.c_void_p]),
+    "ccoll_szx_decompress_static": (ctypes.c_int, [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "ccoll_wait": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_size_t)]),
     "ccoll_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
@@ -90,6 +92,19 @@ def load_library() -> ctypes.CDLL:
 
 def max_compressed_bytes(n: int) -> int:
     return int(load_library().ccoll_szx_max_compressed_bytes(n))
+
+
+STATIC_MAX_ELEMS = 1 << 27
+
+
+def decompress_static(stream, n: int, out, result, in_bytes: int | None = None, device: int = 0, hip_stream=None) -> int:
+    """ccoll_szx_decompress_static: no context, no allocation; {0, status} lands in `result` (int64[2] tensor)."""
+    import torch
+    if hip_stream is None:
+        hip_stream = torch.cuda.current_stream(device).cuda_stream
+    return load_library().ccoll_szx_decompress_static(device, ctypes.c_void_p(hip_stream), _ptr(stream),
+                                                      stream.numel() if in_bytes is None else in_bytes, _ptr(out), n,
+                                                      _ptr(result))
 
 
 class CcollError(RuntimeError):

@@ -22,6 +22,7 @@
 #include <string.h>
 #include <math.h>
 #include <new>
+#include <mutex>
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -1427,7 +1428,33 @@ __global__ void __launch_bounds__(64 * kRedWaves) __attribute__((amdgpu_waves_pe
   reduce_step_body<CCOLL_OP_MIN>(P, sm);
 }
 
+// ---------------------------------------------------------------------------------------------
+// scratch of the entry point that allocates nothing (ccoll_szx_decompress_static)
+// ---------------------------------------------------------------------------------------------
+// What ccoll_szx_decompress keeps in the context's device allocations -- the result / error words and the
+// chunk-start offsets that k_index_scan hands to k_decompress -- in a static device array, so that a caller
+// under stream capture or in a loop that must not allocate can decode without a context.  Every device
+// that runs the library holds its own copy until the process ends.
+constexpr size_t kStaticMaxElems = CCOLL_STATIC_MAX_ELEMS;
+constexpr size_t kStaticMaxChunks = (kStaticMaxElems + kChunk - 1) / kChunk;
+struct StaticScratch {
+  Workspace ws;
+  u64 offs[kStaticMaxChunks + 1];
+};
+
+// The words of the last call are cleared by a kernel, not by a memset, so that the sequence can be captured
+// into a graph and replayed.
+__global__ void k_static_fail(Params P) {
+  if (threadIdx.x == 0) raise_error(P, CCOLL_ECORRUPT, 1);
+}
+__global__ void k_static_begin(Workspace* ws) {
+  if (threadIdx.x == 0) { st_dev(&ws->total, 0ull); st_dev(&ws->err, 0ull); st_dev(&ws->abort, 0ull); }
+}
+
 }  // namespace
+
+// file scope: host code takes its device address with hipGetSymbolAddress, never by its name
+static __device__ __align__(256) unsigned char scratch[(sizeof(StaticScratch) + 255) / 256 * 256];
 
 // ---------------------------------------------------------------------------------------------
 // host side
@@ -1717,6 +1744,56 @@ int ccoll_reduce_step_op_async(ccoll_ctx* c, int op, const float* d_local, size_
 int ccoll_reduce_step_async(ccoll_ctx* c, const float* d_local, size_t n, const void* d_cin, size_t cin_bytes,
                             float abs_eb, void* d_cout, size_t cout_cap, unsigned long long* d_result) {
   return ccoll_reduce_step_op_async(c, CCOLL_OP_SUM, d_local, n, d_cin, cin_bytes, abs_eb, d_cout, cout_cap, d_result);
+}
+
+// Address of the static scratch array on `device`, resolved once per device with that device current (every
+// device has its own copy at its own address).  Host code never uses the array's name as an address.
+static int static_scratch(int device, StaticScratch** out) {
+  constexpr int kMaxDevices = 64;
+  static StaticScratch* ptrs[kMaxDevices];
+  static std::mutex lock;
+  if (device < 0 || device >= kMaxDevices) return CCOLL_EINVAL;
+  std::lock_guard<std::mutex> hold(lock);
+  if (!ptrs[device]) {
+    void* p = nullptr;
+    if (!HIP_OK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) || !p) return CCOLL_EHIP;
+    ptrs[device] = (StaticScratch*)p;
+  }
+  *out = ptrs[device];
+  return CCOLL_OK;
+}
+
+int ccoll_szx_decompress_static(int device, void* hip_stream, const void* d_in, size_t in_bytes, float* d_out, size_t n,
+                                unsigned long long* d_result) {
+  if (!d_in || (!d_out && n) || !d_result) return CCOLL_EINVAL;
+  if (n > kStaticMaxElems) return CCOLL_EINVAL;                 // larger streams need a context (ccoll_szx_decompress)
+  if (((uintptr_t)d_in & 3) || ((uintptr_t)d_out & 3) || ((uintptr_t)d_result & 7)) return CCOLL_EINVAL;
+  DeviceGuard g(device);
+  if (!g.ok) return CCOLL_EHIP;
+  StaticScratch* sc = nullptr;
+  int rc = static_scratch(device, &sc);
+  if (rc) return rc;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  Params P;
+  memset(&P, 0, sizeof(P));
+  P.n = n; P.nchunks = (u32)((n + kChunk - 1) / kChunk); P.c0 = 0; P.c1 = P.nchunks;
+  P.epoch = 1;                                                  // the words are cleared per call, not tagged
+  P.ws = &sc->ws; P.offs = sc->offs; P.spin_limit = kSpinLimit;
+  P.in = d_in; P.in_bytes = in_bytes; P.out = d_out; P.first = 0; P.count = n;
+  P.aligned16 = (((uintptr_t)d_out & 15) == 0);
+  P.result = (u64*)d_result; P.no_total = 1;
+  hipLaunchKernelGGL(k_static_begin, dim3(1), dim3(64), 0, stream, &sc->ws);
+  if (in_bytes < kHeader + 4ull * P.nchunks) {
+    // too short to hold the header and the front index: reported through d_result like every stream error
+    hipLaunchKernelGGL(k_static_fail, dim3(1), dim3(64), 0, stream, P);
+  } else if (n == 0) {
+    hipLaunchKernelGGL(k_check_empty, dim3(1), dim3(64), 0, stream, P);
+  } else {
+    hipLaunchKernelGGL(k_index_scan, dim3((P.nchunks + kScanTile - 1) / kScanTile), dim3(1024), 0, stream, P);
+    hipLaunchKernelGGL(k_decompress, dim3((P.nchunks + kDecWaves - 1) / kDecWaves), dim3(64 * kDecWaves), 0, stream, P);
+  }
+  hipLaunchKernelGGL(k_publish, dim3(1), dim3(1), 0, stream, P);
+  return HIP_OK(hipGetLastError()) ? CCOLL_OK : CCOLL_EHIP;
 }
 
 int ccoll_wait(ccoll_ctx* c, size_t* bytes) {
