@@ -169,6 +169,9 @@ __device__ __forceinline__ u32 lds_load32_any(const unsigned char* base, u32 add
   return __builtin_amdgcn_alignbyte(q[1], q[0], addr);
 }
 __device__ __forceinline__ u32 lds_load16(const unsigned char* p) { unsigned short s; __builtin_memcpy(&s, p, 2); return s; }
+// OR into an aligned LDS word.  Only the wavefront that owns the word touches it; LDS executes a wavefront's
+// operations in order, so later reads of the word by the same wavefront see the result.
+__device__ __forceinline__ void lds_or32(u32* p, u32 v) { __hip_atomic_fetch_or(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT); }
 
 // Device-scope relaxed atomics: they bypass the per-XCD L2, so workgroups on different XCDs see each
 // other's words without any cache write-back or invalidate.
@@ -1047,16 +1050,74 @@ __device__ __forceinline__ void write_body(const EncRegs& r, unsigned char* body
   }
 }
 
+// The same for blocks without raw elements (at most 3 bytes per element), without any predication: the stage
+// is all zeros where nothing has been written yet, and a lane ORs whole aligned words into it.
+//   * A lane's elements go four at a time.  The up to 12 bytes of four elements are first gathered in three
+//     registers as a byte-reversed string: elements are pushed last to first, a push is {t, A} >> 8c (the low c
+//     bytes of t are exactly the bytes to emit, least significant first, and v_alignbyte takes c from the two
+//     low bits of its operand, so c = 0 needs no special case).  After the four pushes the reversed string
+//     sits at the top of the three registers, zeros below.
+//   * One v_perm per output word then reverses the bytes back and shifts the string to the byte position
+//     (p & 3) of its place in the stage; four words at most are touched, and words or bytes that belong to a
+//     neighbour (the lane before, the next group, the next block) receive zeros.
+// `off`: byte offset of the block's body in the stage; body32: the stage as words (16-byte aligned).
+template <bool FULL>
+__device__ __forceinline__ void write_body_or(const EncRegs& r, u32* body32, u32 off) {
+  const u32 l8 = threadIdx.x & 7u;
+  {
+    // the lane's four bytes of lead codes at byte offset q: word 0 gets lc << 8a, word 1 gets lc >> (32 - 8a), a = q & 3
+    const u32 q = off + 4u * l8;
+    const u32 sel = __builtin_amdgcn_alignbyte(0x00070605u, 0x04030201u, ~q);     // bytes 4-a, 5-a, 6-a, 7-a
+    u32* w = body32 + (q >> 2);
+    if (FULL || 4u * l8 < r.nlead) {
+      lds_or32(w, __builtin_amdgcn_perm(r.lc, 0u, sel));
+      lds_or32(w + 1, __builtin_amdgcn_perm(0u, r.lc, sel));
+    }
+  }
+  const u32 cc = r.cc;
+  // bytes of each group of four elements, and their running sums, one per byte
+  const u32 pr = (cc & 0x33333333u) + ((cc >> 2) & 0x33333333u);
+  const u32 gs = (pr + (pr >> 4)) & 0x0f0f0f0fu;
+  u32 run = gs + (gs << 8); run += run << 16;
+  const u32 p0 = off + r.nlead + (r.incl - r.len);
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const u32 c0 = cc >> (8 * g), c1 = cc >> (8 * g + 2), c2 = cc >> (8 * g + 4), c3 = cc >> (8 * g + 6);
+    u32 a2 = __builtin_amdgcn_alignbyte(r.t[4 * g + 3], 0u, c3);
+    u32 a1 = __builtin_amdgcn_alignbyte(a2, 0u, c2);
+    a2 = __builtin_amdgcn_alignbyte(r.t[4 * g + 2], a2, c2);
+    u32 a0 = __builtin_amdgcn_alignbyte(a1, 0u, c1);
+    a1 = __builtin_amdgcn_alignbyte(a2, a1, c1);
+    a2 = __builtin_amdgcn_alignbyte(r.t[4 * g + 1], a2, c1);
+    a0 = __builtin_amdgcn_alignbyte(a1, a0, c0);
+    a1 = __builtin_amdgcn_alignbyte(a2, a1, c0);
+    a2 = __builtin_amdgcn_alignbyte(r.t[4 * g], a2, c0);
+    const u32 p = g == 0 ? p0 : p0 + ((run >> (8 * (g - 1))) & 0xffu);
+    const u32 sel = __builtin_amdgcn_alignbyte(0x00000102u, 0x03040506u, ~p);    // bytes a+3, a+2, a+1, a with a = p & 3
+    u32* w = body32 + (p >> 2);
+    lds_or32(w, __builtin_amdgcn_perm(0u, a2, sel));
+    lds_or32(w + 1, __builtin_amdgcn_perm(a2, a1, sel));
+    lds_or32(w + 2, __builtin_amdgcn_perm(a1, a0, sel));
+    lds_or32(w + 3, __builtin_amdgcn_perm(a0, 0u, sel));
+  }
+}
+
 // n bytes (a multiple of 4) from a 16-byte aligned LDS address to a 4-byte aligned global address.
-__device__ __forceinline__ void copy_out(unsigned char* dst, const unsigned char* src, u32 n) {
+// ZERO: the LDS bytes are set to zero behind the copy (a stage must be all zeros before bodies are ORed into it).
+template <bool ZERO>
+__device__ __forceinline__ void copy_out(unsigned char* dst, unsigned char* src, u32 n) {
   const u32 lane = threadIdx.x & 63u;
   const u32 n16 = n >> 4;
   for (u32 i = lane; i < n16; i += 64u) {
     const uint4 v = *(const uint4*)(src + 16u * i);
+    if (ZERO) *(uint4*)(src + 16u * i) = make_uint4(0, 0, 0, 0);
     __builtin_memcpy(dst + 16u * i, &v, 16);
   }
   const u32 rest = (n >> 2) & 3u;
-  if (lane < rest) ((u32*)(dst + 16u * n16))[lane] = ((const u32*)(src + 16u * n16))[lane];
+  if (lane < rest) {
+    ((u32*)(dst + 16u * n16))[lane] = ((const u32*)(src + 16u * n16))[lane];
+    if (ZERO) ((u32*)(src + 16u * n16))[lane] = 0u;
+  }
 }
 
 // n bytes (a multiple of 4) between global addresses: src 16-byte aligned, dst 4-byte aligned.
@@ -1129,9 +1190,9 @@ __device__ __forceinline__ u32 encode_unit(const u32 (&xb)[kE], int nv, int blen
   const u32 total = (u32)__builtin_amdgcn_readlane((int)sc, 63);
   if (bodybase - flushed + total > CAP) {                                 // make room: at most 15 + 8 * 544 bytes are needed
     const u32 fill = bodybase - flushed, n = fill & ~15u;
-    copy_out(slot + kMetaMax + flushed, L.body, n);
+    copy_out<true>(slot + kMetaMax + flushed, L.body, n);
     unsigned char keep = 0;
-    if (lane < fill - n) keep = L.body[n + lane];
+    if (lane < fill - n) { keep = L.body[n + lane]; L.body[n + lane] = 0; }
     if (lane < fill - n) L.body[lane] = keep;
     flushed += n;
   }
@@ -1141,10 +1202,8 @@ __device__ __forceinline__ u32 encode_unit(const u32 (&xb)[kE], int nv, int blen
     L.tmp[blk] = v | ((rc.type == 0 ? 0u : (rc.type == 2 ? 32u : 9u + rc.m)) << 16);
   }
   if (r.active) {
-    unsigned char* body = L.body + start;
-    if (r.anyraw) write_body<FULL, true, false>(r, body);
-    else if (__ballot(r.active && r.nb != 2u) == 0) write_body<FULL, false, true>(r, body);
-    else write_body<FULL, false, false>(r, body);
+    if (r.anyraw) write_body<FULL, true, false>(r, L.body + start);
+    else write_body_or<FULL>(r, (u32*)L.body, start);
   }
   return total;
 }
@@ -1195,8 +1254,7 @@ __device__ __forceinline__ ChunkOut encode_chunk(Src& src, u32 c, const Params& 
   unsigned char* m8 = (unsigned char*)L.meta;
   if (lane == 0) {
     L.meta[0] = (u32)bitmap; L.meta[1] = (u32)(bitmap >> 32);
-    for (u32 i = meta_raw; i < o.meta_len; ++i) m8[i] = 0;
-    for (u32 i = bodybase; i < pad4(bodybase); ++i) L.body[i - flushed] = 0;
+    for (u32 i = meta_raw; i < o.meta_len; ++i) m8[i] = 0;            // the stage's body bytes behind the last body are zeros already
   }
   if (rq != 0) {
     lds_store16(m8 + 8 + 4 * nbc + 2 * rank, bs);
@@ -1219,8 +1277,8 @@ __device__ __forceinline__ void write_header(const Params& P, u64 total) {
 // What is still in the LDS stage of a coded chunk joins the rest in the spill slot (the payload is parked).
 template <u32 CAP>
 __device__ __forceinline__ void park_chunk(const ChunkOut& o, unsigned char* slot, EncWaveLds<CAP>& L) {
-  copy_out(slot, (const unsigned char*)L.meta, o.meta_len);
-  copy_out(slot + kMetaMax + o.flushed, L.body, pad4(o.bodies) - o.flushed);
+  copy_out<false>(slot, (unsigned char*)L.meta, o.meta_len);
+  copy_out<true>(slot + kMetaMax + o.flushed, L.body, pad4(o.bodies) - o.flushed);
 }
 
 // The payload of chunk c goes to its place `off` bytes into the payload area: from the spill slot, or, if it
@@ -1243,8 +1301,8 @@ __device__ __forceinline__ void place_chunk(u32 c, const ChunkOut& o, u64 off, b
     copy_gg(dst, slot, o.meta_len);
     copy_gg(dst + o.meta_len, slot + kMetaMax, nb);
   } else {
-    copy_out(dst, (const unsigned char*)L.meta, o.meta_len);
-    copy_out(dst + o.meta_len, L.body, nb);
+    copy_out<false>(dst, (unsigned char*)L.meta, o.meta_len);
+    copy_out<true>(dst + o.meta_len, L.body, nb);
   }
 }
 
@@ -1261,9 +1319,9 @@ __device__ __forceinline__ void place_staged(u32 c, const ChunkOut& o, u64 off, 
   }
   if (!fits) return;
   unsigned char* dst = (unsigned char*)P.out + front + off;
-  copy_out(dst, (const unsigned char*)L.meta, o.meta_len);
+  copy_out<false>(dst, (unsigned char*)L.meta, o.meta_len);
   if (o.flushed) copy_gg(dst + o.meta_len, slot + kMetaMax, o.flushed);
-  copy_out(dst + o.meta_len + o.flushed, L.body, pad4(o.bodies) - o.flushed);
+  copy_out<true>(dst + o.meta_len + o.flushed, L.body, pad4(o.bodies) - o.flushed);
 }
 
 template <int NW>
@@ -1293,6 +1351,10 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
   // while the chunk being coded outgrows the LDS stage into the other
   unsigned char* slots = P.spill + ((u64)blockIdx.x * NW + wv) * 2u * slot_bytes;
 
+  // bodies are ORed into the stages: they start as zeros, and every copy out of a stage leaves zeros behind
+#pragma unroll
+  for (int i = 0; i < NS; ++i)
+    for (u32 j = lane; j < (CAP + 16u) / 16u; j += 64u) *(uint4*)(Ls[i].body + 16u * j) = make_uint4(0, 0, 0, 0);
   u64* ticket = &P.ws->ticket[P.ticket_sel];
   if (threadIdx.x == 0) {
     if (blockIdx.x == 0) st_dev(&P.ws->ticket[P.ticket_sel ^ 1u], 0ull);      // for the next launch on the stream
