@@ -1061,7 +1061,7 @@ __device__ __forceinline__ void write_body(const EncRegs& r, unsigned char* body
 //     (p & 3) of its place in the stage; four words at most are touched, and words or bytes that belong to a
 //     neighbour (the lane before, the next group, the next block) receive zeros.
 // `off`: byte offset of the block's body in the stage; body32: the stage as words (16-byte aligned).
-template <bool FULL>
+template <bool FULL, bool NB2>
 __device__ __forceinline__ void write_body_or(const EncRegs& r, u32* body32, u32 off) {
   const u32 l8 = threadIdx.x & 7u;
   {
@@ -1083,35 +1083,62 @@ __device__ __forceinline__ void write_body_or(const EncRegs& r, u32* body32, u32
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
     const u32 c0 = cc >> (8 * g), c1 = cc >> (8 * g + 2), c2 = cc >> (8 * g + 4), c3 = cc >> (8 * g + 6);
-    u32 a2 = __builtin_amdgcn_alignbyte(r.t[4 * g + 3], 0u, c3);
-    u32 a1 = __builtin_amdgcn_alignbyte(a2, 0u, c2);
-    a2 = __builtin_amdgcn_alignbyte(r.t[4 * g + 2], a2, c2);
-    u32 a0 = __builtin_amdgcn_alignbyte(a1, 0u, c1);
-    a1 = __builtin_amdgcn_alignbyte(a2, a1, c1);
-    a2 = __builtin_amdgcn_alignbyte(r.t[4 * g + 1], a2, c1);
-    a0 = __builtin_amdgcn_alignbyte(a1, a0, c0);
-    a1 = __builtin_amdgcn_alignbyte(a2, a1, c0);
-    a2 = __builtin_amdgcn_alignbyte(r.t[4 * g], a2, c0);
     const u32 p = g == 0 ? p0 : p0 + ((run >> (8 * (g - 1))) & 0xffu);
     const u32 sel = __builtin_amdgcn_alignbyte(0x00000102u, 0x03040506u, ~p);    // bytes a+3, a+2, a+1, a with a = p & 3
     u32* w = body32 + (p >> 2);
-    lds_or32(w, __builtin_amdgcn_perm(0u, a2, sel));
-    lds_or32(w + 1, __builtin_amdgcn_perm(a2, a1, sel));
-    lds_or32(w + 2, __builtin_amdgcn_perm(a1, a0, sel));
-    lds_or32(w + 3, __builtin_amdgcn_perm(a0, 0u, sel));
+    if (NB2) {
+      // at most 2 bytes per element: 8 bytes per group, two registers, three words
+      u32 a1 = __builtin_amdgcn_alignbyte(r.t[4 * g + 3], 0u, c3);
+      a1 = __builtin_amdgcn_alignbyte(r.t[4 * g + 2], a1, c2);
+      u32 a0 = __builtin_amdgcn_alignbyte(a1, 0u, c1);
+      a1 = __builtin_amdgcn_alignbyte(r.t[4 * g + 1], a1, c1);
+      a0 = __builtin_amdgcn_alignbyte(a1, a0, c0);
+      a1 = __builtin_amdgcn_alignbyte(r.t[4 * g], a1, c0);
+      lds_or32(w, __builtin_amdgcn_perm(0u, a1, sel));
+      lds_or32(w + 1, __builtin_amdgcn_perm(a1, a0, sel));
+      lds_or32(w + 2, __builtin_amdgcn_perm(a0, 0u, sel));
+    } else {
+      u32 a2 = __builtin_amdgcn_alignbyte(r.t[4 * g + 3], 0u, c3);
+      u32 a1 = __builtin_amdgcn_alignbyte(a2, 0u, c2);
+      a2 = __builtin_amdgcn_alignbyte(r.t[4 * g + 2], a2, c2);
+      u32 a0 = __builtin_amdgcn_alignbyte(a1, 0u, c1);
+      a1 = __builtin_amdgcn_alignbyte(a2, a1, c1);
+      a2 = __builtin_amdgcn_alignbyte(r.t[4 * g + 1], a2, c1);
+      a0 = __builtin_amdgcn_alignbyte(a1, a0, c0);
+      a1 = __builtin_amdgcn_alignbyte(a2, a1, c0);
+      a2 = __builtin_amdgcn_alignbyte(r.t[4 * g], a2, c0);
+      lds_or32(w, __builtin_amdgcn_perm(0u, a2, sel));
+      lds_or32(w + 1, __builtin_amdgcn_perm(a2, a1, sel));
+      lds_or32(w + 2, __builtin_amdgcn_perm(a1, a0, sel));
+      lds_or32(w + 3, __builtin_amdgcn_perm(a0, 0u, sel));
+    }
   }
 }
 
-// n bytes (a multiple of 4) from a 16-byte aligned LDS address to a 4-byte aligned global address.
 // ZERO: the LDS bytes are set to zero behind the copy (a stage must be all zeros before bodies are ORed into it).
+// Four vectors per lane are read before the first one is stored, so that a payload of up to 4 KB costs one
+// LDS round trip.
 template <bool ZERO>
 __device__ __forceinline__ void copy_out(unsigned char* dst, unsigned char* src, u32 n) {
   const u32 lane = threadIdx.x & 63u;
   const u32 n16 = n >> 4;
-  for (u32 i = lane; i < n16; i += 64u) {
-    const uint4 v = *(const uint4*)(src + 16u * i);
-    if (ZERO) *(uint4*)(src + 16u * i) = make_uint4(0, 0, 0, 0);
-    __builtin_memcpy(dst + 16u * i, &v, 16);
+  constexpr int kBatch = 4;
+  for (u32 j0 = 0; j0 < n16; j0 += 64u * kBatch) {
+    uint4 v[kBatch];
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const u32 j = j0 + lane + 64u * (u32)i;
+      v[i] = make_uint4(0, 0, 0, 0);
+      if (j < n16) v[i] = *(const uint4*)(src + 16u * j);
+    }
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const u32 j = j0 + lane + 64u * (u32)i;
+      if (j < n16) {
+        if (ZERO) *(uint4*)(src + 16u * j) = make_uint4(0, 0, 0, 0);
+        __builtin_memcpy(dst + 16u * j, &v[i], 16);
+      }
+    }
   }
   const u32 rest = (n >> 2) & 3u;
   if (lane < rest) {
@@ -1203,7 +1230,8 @@ __device__ __forceinline__ u32 encode_unit(const u32 (&xb)[kE], int nv, int blen
   }
   if (r.active) {
     if (r.anyraw) write_body<FULL, true, false>(r, L.body + start);
-    else write_body_or<FULL>(r, (u32*)L.body, start);
+    else if (__ballot(r.nb != 2u) == 0) write_body_or<FULL, true>(r, (u32*)L.body, start);     // active lanes only
+    else write_body_or<FULL, false>(r, (u32*)L.body, start);
   }
   return total;
 }
