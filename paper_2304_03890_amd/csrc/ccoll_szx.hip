@@ -28,6 +28,10 @@
 
 #include "../../include/ccoll_szx.h"
 
+#ifndef CCOLL_RED_OCC
+#define CCOLL_RED_OCC 3
+#endif
+
 namespace {
 
 typedef uint32_t u32;
@@ -925,42 +929,108 @@ __device__ __forceinline__ void load_unit(const float* base, u64 n, u32 c, int u
 struct SrcPlain {                                     // compress: the floats themselves
   static constexpr bool kPrefetch = true;             // a unit's floats are requested while the one before is coded
   const float* in; bool al;
-  __device__ __forceinline__ void begin_chunk(u32, const Params&) {}
+  __device__ __forceinline__ void begin_chunk(u32, const Params&, unsigned char*) {}
   template <bool FULL>
   __device__ __forceinline__ void load(const Params& P, u32 c, int u, u32 (&xb)[kE], int& nv, int& blen) const {
     load_unit<FULL>(in, P.n, c, u, al, xb, nv, blen);
   }
+  __device__ __forceinline__ bool needs_room(const Params&, u32, int, u32) { return false; }
+  __device__ __forceinline__ void fetch(const Params&, u32, int, u32) {}
   template <bool FULL>
   __device__ __forceinline__ void finish(const Params&, u32, int, u32 (&)[kE], int, int, const GrpMasks&) {}
+  __device__ __forceinline__ void make_room(u32) {}
+  __device__ __forceinline__ void end_chunk() {}
 };
 
-constexpr u32 kWinR = 5888;                             // the reduce step's window (>= one unit's bodies, 8 * 544 + 3): most payloads whole
-constexpr u32 kRegionR = kWinPad + kWinR + 576;
-template <int OP>
+// The reduce step keeps its window of the incoming payload inside the LDS stage it is coding into: the coded
+// bodies grow from the front of the stage, the window sits at its end and holds the bodies of the units that
+// are still to be decoded.  (A window of its own next to two stages per wavefront does not fit a compute unit's
+// LDS at three wavefronts per SIMD.)  Where the coded bodies reach the window, its front is given up (zeroed:
+// bodies are ORed into zeros); as a rule that front has been decoded by then.  If bodies that are still needed
+// are lost that way, or did not fit in the first place, they are fetched again behind the coded bodies.
+template <int OP, u32 CAP>
 struct SrcReduce {                                    // reduce step: local floats (+, max, min) the incoming chunk, decoded
   static constexpr bool kPrefetch = false;            // registers are short: the decoder needs them
+  static constexpr u32 kEnd = CAP + 16u;              // size of a stage's body area
   const float* local; bool al;
   const unsigned char* s;                             // incoming stream
-  unsigned char* win;                                 // the wavefront's window of the incoming payload (LDS, past its pad)
-  const unsigned char* src; u32 payload, wbase, wend; bool good;
+  unsigned char* stage;                               // body area of the stage being coded into (16-byte aligned)
+  const unsigned char* src; u32 payload; bool good;
+  u32 wbase, wlen, wpos;                              // payload bytes [wbase, wbase + wlen) are at stage[wpos ...); wlen = 0: no window
   ChunkMeta m;
-  __device__ __forceinline__ void begin_chunk(u32 c, const Params& P) {
+  // bytes between the coded bodies (the writer touches up to 16 bytes past its last body) and the end of the stage
+  static __device__ __forceinline__ u32 room_behind(u32 fill) {
+    const u32 used = ((fill + 31u) & ~15u) + 16u;
+    return used < kEnd ? kEnd - used : 0u;
+  }
+  __device__ __forceinline__ void zero_window() {
     const u32 lane = threadIdx.x & 63u;
+    for (u32 j = (wpos >> 4) + lane; j < kEnd / 16u; j += 64u) *(uint4*)(stage + 16u * j) = make_uint4(0, 0, 0, 0);
+    wlen = 0;
+  }
+  // Window <- payload bytes from `from` on, as many as fit between the coded bodies (`fill` bytes) and the end.
+  __device__ __forceinline__ void fetch_from(u32 from, u32 fill) {
+    if (wlen) zero_window();
+    const u32 room = room_behind(fill);
+    u32 len = payload - from; len = len < room ? len : room;
+    wpos = kEnd - ((len + 15u) & ~15u);
+    fetch_window(src, from, len, stage + wpos);
+    wbase = from; wlen = len;
+  }
+  __device__ __forceinline__ void begin_chunk(u32 c, const Params& P, unsigned char* stage_body) {
+    const u32 lane = threadIdx.x & 63u;
+    stage = stage_body;
     const InChunk cur = locate_chunk(s, c, P, 0u);
-    good = cur.ok; src = cur.src; payload = cur.size; wbase = 0; wend = 0;
+    good = cur.ok; src = cur.src; payload = cur.size; wbase = 0; wlen = 0; wpos = kEnd;
     m.rq = 0; m.bs = 0; m.boff = 0; m.end = 0; m.mu = 0.0f;
     if (!good) { if (lane == 0) raise_error(P, CCOLL_ECORRUPT, 4); return; }
-    wend = payload < kWinR ? payload : kWinR;
-    fetch_window(src, 0, wend, win);
+    fetch_from(0, 0);
     const u64 cbeg = (u64)c * kChunk;
     const int nbc = P.n - cbeg >= (u64)kChunk ? kBpc : (int)((P.n - cbeg + kBlock - 1) / kBlock);
-    good = parse_meta(win, payload, nbc, m);
+    good = parse_meta(stage + wpos, payload, nbc, m);
     if (!good && lane == 0) raise_error(P, CCOLL_ECORRUPT, 6);
   }
   template <bool FULL>
   __device__ __forceinline__ void load(const Params& P, u32 c, int u, u32 (&xb)[kE], int& nv, int& blen) const {
     load_unit<FULL>(local, P.n, c, u, al, xb, nv, blen);
   }
+  // bodies of unit u of the incoming chunk: payload bytes [ustart, uend)
+  __device__ __forceinline__ void unit_span(const Params& P, u32 c, int u, u32& ustart, u32& uend) const {
+    const u64 left = P.n - (u64)c * kChunk;
+    const int nbc = left >= (u64)kChunk ? kBpc : (int)((left + kBlock - 1) / kBlock);
+    const int last = 8 * u + 7 < nbc ? 8 * u + 7 : nbc - 1;
+    ustart = (u32)__builtin_amdgcn_readlane((int)m.boff, 8 * u);
+    uend = (u32)__builtin_amdgcn_readlane((int)m.end, last);
+  }
+  // True: unit u is not in the window and there is no room for its bodies behind the `fill` coded bytes: the
+  // caller moves the coded bytes on to the spill slot first.
+  __device__ __forceinline__ bool needs_room(const Params& P, u32 c, int u, u32 fill) {
+    if (!good) return false;
+    u32 ustart, uend; unit_span(P, c, u, ustart, uend);
+    if (ustart >= wbase && uend <= wbase + wlen) return false;
+    return uend - (ustart & ~3u) > room_behind(fill);
+  }
+  // Brings unit u's bodies into the window if they are not there.
+  __device__ __forceinline__ void fetch(const Params& P, u32 c, int u, u32 fill) {
+    if (!good) return;
+    u32 ustart, uend; unit_span(P, c, u, ustart, uend);
+    if (ustart >= wbase && uend <= wbase + wlen) return;
+    fetch_from(ustart & ~3u, fill);
+  }
+  // The coder is about to write up to byte `upto` of the stage: the front of the window that is in its way is
+  // given up.  As a rule that front holds the metadata and the bodies of units that have been decoded already,
+  // and the rest of the window stays in use.
+  __device__ __forceinline__ void make_room(u32 upto) {
+    if (wlen && upto + 16u > wpos) {
+      const u32 lane = threadIdx.x & 63u;
+      u32 z = (upto + 31u) & ~15u; z = z < kEnd ? z : kEnd;
+      for (u32 j = (wpos >> 4) + lane; j < (z >> 4); j += 64u) *(uint4*)(stage + 16u * j) = make_uint4(0, 0, 0, 0);
+      const u32 d = z - wpos;
+      if (d >= wlen) wlen = 0;
+      else { wbase += d; wlen -= d; wpos = z; }
+    }
+  }
+  __device__ __forceinline__ void end_chunk() { if (wlen) zero_window(); }
   // xb: local floats in, sums out (Eq. 2: one float32 round-to-nearest add per element).  If the incoming
   // chunk cannot be read, 0 stands in for it so that the outgoing stream is still well formed; the error
   // has been raised.
@@ -970,17 +1040,8 @@ struct SrcReduce {                                    // reduce step: local floa
     const int b = 8 * u + (int)(lane >> 3);
     BlockInfo bi; bi.rq = 0; bi.bs = 0; bi.boff = 0;
     float mu = 0.0f;
+    const unsigned char* win = stage + wpos;
     if (good) {
-      const int nbc = FULL ? kBpc : (int)((P.n - (u64)c * kChunk + kBlock - 1) / kBlock);
-      const int last = FULL ? 8 * u + 7 : (8 * u + 7 < nbc ? 8 * u + 7 : nbc - 1);
-      const u32 ustart = (u32)__builtin_amdgcn_readlane((int)m.boff, 8 * u);
-      const u32 uend = (u32)__builtin_amdgcn_readlane((int)m.end, last);
-      if (ustart < wbase || uend > wend) {                             // slide the window to this unit's bodies
-        wbase = ustart & ~3u;
-        const u32 len = payload - wbase < kWinR ? payload - wbase : kWinR;
-        wend = wbase + len;
-        fetch_window(src, wbase, len, win);
-      }
       bi.rq = (u32)__shfl((int)m.rq, b); bi.bs = (u32)__shfl((int)m.bs, b);
       bi.boff = (u32)__shfl((int)m.boff, b) - wbase;
       mu = __shfl(m.mu, b);
@@ -1198,9 +1259,22 @@ __device__ __forceinline__ void copy_in(unsigned char* dst, const unsigned char*
 // stage; when a unit does not fit behind what is staged, the staged bytes (all but the last < 16) move on to
 // the wavefront's spill slot and the stage starts over: `flushed` counts the body bytes already in the slot.
 // Returns the body bytes of the unit.
-template <bool FULL, u32 CAP>
+// The staged body bytes (all but the last < 16) move on to the wavefront's spill slot; the stage starts over.
+template <u32 CAP>
+__device__ __forceinline__ void flush_stage(EncWaveLds<CAP>& L, u32 bodybase, u32& flushed, unsigned char* slot) {
+  const u32 lane = threadIdx.x & 63u;
+  const u32 fill = bodybase - flushed, n = fill & ~15u;
+  copy_out<true>(slot + kMetaMax + flushed, L.body, n);
+  unsigned char keep = 0;
+  if (lane < fill - n) { keep = L.body[n + lane]; L.body[n + lane] = 0; }
+  if (lane < fill - n) L.body[lane] = keep;
+  flushed += n;
+}
+
+template <bool FULL, u32 CAP, class Src>
 __device__ __forceinline__ u32 encode_unit(const u32 (&xb)[kE], int nv, int blen, int blk, int nbc, const Params& P,
-                                           const GrpMasks& gm, EncWaveLds<CAP>& L, u32 bodybase, u32& flushed, unsigned char* slot) {
+                                           const GrpMasks& gm, EncWaveLds<CAP>& L, u32 bodybase, u32& flushed, unsigned char* slot,
+                                           Src& src) {
   const u32 lane = threadIdx.x & 63u, l8 = lane & 7u;
   const bool exists = FULL || blen > 0;
   const RowClass rc = classify_row(xb, P.eb, P.e_eb);
@@ -1215,14 +1289,8 @@ __device__ __forceinline__ u32 encode_unit(const u32 (&xb)[kE], int nv, int blen
   const u32 v = (l8 == kGrp - 1 && r.active) ? r.nlead + r.incl : 0u;     // the block's body bytes, at its last lane
   const u32 sc = wave_scan_add(v);
   const u32 total = (u32)__builtin_amdgcn_readlane((int)sc, 63);
-  if (bodybase - flushed + total > CAP) {                                 // make room: at most 15 + 8 * 544 bytes are needed
-    const u32 fill = bodybase - flushed, n = fill & ~15u;
-    copy_out<true>(slot + kMetaMax + flushed, L.body, n);
-    unsigned char keep = 0;
-    if (lane < fill - n) { keep = L.body[n + lane]; L.body[n + lane] = 0; }
-    if (lane < fill - n) L.body[lane] = keep;
-    flushed += n;
-  }
+  if (bodybase - flushed + total > CAP) flush_stage<CAP>(L, bodybase, flushed, slot);   // make room: at most 15 + 8 * 544 bytes are needed
+  src.make_room(bodybase - flushed + total);                              // a window of the source in the way is given up
   const u32 start = bodybase - flushed + sc - v;                          // in the stage; the same for all lanes of a block
   if (l8 == kGrp - 1 && blk < nbc) {
     L.meta[2 + blk] = f2u(rc.mu);
@@ -1247,7 +1315,7 @@ __device__ __forceinline__ ChunkOut encode_chunk(Src& src, u32 c, const Params& 
   const u32 lane = threadIdx.x & 63u;
   const int nbc = FULL ? kBpc : (int)((P.n - (u64)c * kChunk + kBlock - 1) / kBlock);
   const int nunits = FULL ? kUnits : (nbc + 7) / 8;
-  src.begin_chunk(c, P);
+  src.begin_chunk(c, P, L.body);
   u32 xa[kE]; int nv, blen;
   src.template load<FULL>(P, c, 0, xa, nv, blen);
   u32 bodybase = 0, flushed = 0;
@@ -1258,7 +1326,7 @@ __device__ __forceinline__ ChunkOut encode_chunk(Src& src, u32 c, const Params& 
       u32 xn[kE]; int nvn = 0, blenn = 0;
       if (u + 1 < nunits) src.template load<FULL>(P, c, u + 1, xn, nvn, blenn);     // in flight while this unit is coded
       src.template finish<FULL>(P, c, u, xa, nv, blen, gm);
-      bodybase += encode_unit<FULL, CAP>(xa, nv, blen, blk, nbc, P, gm, L, bodybase, flushed, slot);
+      bodybase += encode_unit<FULL, CAP>(xa, nv, blen, blk, nbc, P, gm, L, bodybase, flushed, slot, src);
       if (u + 1 < nunits) {
 #pragma unroll
         for (int k = 0; k < kE; ++k) xa[k] = xn[k];
@@ -1266,10 +1334,13 @@ __device__ __forceinline__ ChunkOut encode_chunk(Src& src, u32 c, const Params& 
       }
     } else {
       if (u > 0) src.template load<FULL>(P, c, u, xa, nv, blen);
+      if (src.needs_room(P, c, u, bodybase - flushed)) flush_stage<CAP>(L, bodybase, flushed, slot);
+      src.fetch(P, c, u, bodybase - flushed);
       src.template finish<FULL>(P, c, u, xa, nv, blen, gm);
-      bodybase += encode_unit<FULL, CAP>(xa, nv, blen, blk, nbc, P, gm, L, bodybase, flushed, slot);
+      bodybase += encode_unit<FULL, CAP>(xa, nv, blen, blk, nbc, P, gm, L, bodybase, flushed, slot, src);
     }
   }
+  src.end_chunk();
   // metadata: lane j = block j
   const u32 tv = (int)lane < nbc ? L.tmp[lane] : 0u;
   const u32 rq = tv >> 16, bs = tv & 0xffffu;
@@ -1485,35 +1556,33 @@ __global__ void __launch_bounds__(64 * kEncWaves) __attribute__((amdgpu_waves_pe
   encode_groups<kEncWaves, kEncCap, 2>(src, P, sm.g, sm.wave[threadIdx.x >> 6], kSpillSlot);
 }
 
-// reduce step: 4 wavefronts per workgroup (each also holds a window of the incoming payload), three
-// workgroups per compute unit
+// reduce step: 4 wavefronts per workgroup, three workgroups per compute unit; two stages per wavefront like
+// compress, the window of the incoming payload lives in the stage being coded into
 constexpr int kRedWaves = 4;
-constexpr u32 kRedCap = 6288;
+constexpr u32 kRedCap = 6240;
 struct __align__(16) ReduceSmem {
-  EncWaveLds<kRedCap> wave[kRedWaves];
-  unsigned char win[kRedWaves][kRegionR];
+  EncWaveLds<kRedCap> wave[kRedWaves][2];
   GroupLds<kRedWaves> g;
 };
-static_assert(kMetaMax + kBpc * kMaxBody + 16 <= kSpillSlot && kRedCap >= 8 * kMaxBody + 16, "spill slot, stage");
-static_assert(kWinR % 16 == 0 && kWinR >= 8 * kMaxBody + 3, "window geometry");
+static_assert(kMetaMax + kBpc * kMaxBody + 16 <= kSpillSlot && kRedCap >= 8 * kMaxBody + 64, "spill slot, stage");
 
 template <int OP>
 __device__ __forceinline__ void reduce_step_body(const Params& P, ReduceSmem& sm) {
   const u32 wv = threadIdx.x >> 6;
-  SrcReduce<OP> src; src.local = P.local; src.al = P.aligned16 != 0; src.s = (const unsigned char*)P.cin;
-  src.win = sm.win[wv] + kWinPad; src.src = nullptr; src.payload = 0; src.wbase = 0; src.wend = 0; src.good = false;
-  encode_groups<kRedWaves, kRedCap, 1>(src, P, sm.g, &sm.wave[wv], kSpillSlot);
+  SrcReduce<OP, kRedCap> src; src.local = P.local; src.al = P.aligned16 != 0; src.s = (const unsigned char*)P.cin;
+  src.stage = nullptr; src.src = nullptr; src.payload = 0; src.wbase = 0; src.wlen = 0; src.wpos = 0; src.good = false;
+  encode_groups<kRedWaves, kRedCap, 2>(src, P, sm.g, sm.wave[wv], kSpillSlot);
 }
 // one kernel per reduction, so that the sum carries nothing of the others
-__global__ void __launch_bounds__(64 * kRedWaves) __attribute__((amdgpu_waves_per_eu(3, 3))) k_reduce_step(Params P) {
+__global__ void __launch_bounds__(64 * kRedWaves) __attribute__((amdgpu_waves_per_eu(CCOLL_RED_OCC, CCOLL_RED_OCC))) k_reduce_step(Params P) {
   __shared__ ReduceSmem sm;
   reduce_step_body<CCOLL_OP_SUM>(P, sm);
 }
-__global__ void __launch_bounds__(64 * kRedWaves) __attribute__((amdgpu_waves_per_eu(3, 3))) k_reduce_step_max(Params P) {
+__global__ void __launch_bounds__(64 * kRedWaves) __attribute__((amdgpu_waves_per_eu(CCOLL_RED_OCC, CCOLL_RED_OCC))) k_reduce_step_max(Params P) {
   __shared__ ReduceSmem sm;
   reduce_step_body<CCOLL_OP_MAX>(P, sm);
 }
-__global__ void __launch_bounds__(64 * kRedWaves) __attribute__((amdgpu_waves_per_eu(3, 3))) k_reduce_step_min(Params P) {
+__global__ void __launch_bounds__(64 * kRedWaves) __attribute__((amdgpu_waves_per_eu(CCOLL_RED_OCC, CCOLL_RED_OCC))) k_reduce_step_min(Params P) {
   __shared__ ReduceSmem sm;
   reduce_step_body<CCOLL_OP_MIN>(P, sm);
 }
