@@ -56,7 +56,9 @@ extern "C" {
 
 typedef struct ccoll_ctx ccoll_ctx;
 
-/* One context = one device + one stream + a small scan workspace.
+/* One context = one device + one stream + a scan workspace (16 bytes per chunk of the largest input reserved
+ * for, plus spill slots for chunks that outgrow on-chip staging: 44.5 KB per wavefront of the widest launch,
+ * at most 137 MB).  On failure *out is NULL.
  * hip_stream is a hipStream_t (NULL = the default stream).  Not thread-safe: calls on one
  * context must not overlap. */
 int  ccoll_create(ccoll_ctx **out, int device, void *hip_stream);
@@ -76,7 +78,8 @@ size_t ccoll_szx_max_compressed_bytes(size_t n);
 /* Compression of d_in[0..n) under abs_eb (Sec. III-C fixed-accuracy mode; chunk layout of
  * Sec. III-E.2).  d_in: device, 4-byte aligned (16-byte alignment takes the fast path).
  * d_out: device, 4-byte aligned, out_cap bytes.  out_bytes (host) receives the stream size.
- * CCOLL_ENOSPC if out_cap is too small (then *out_bytes is the size that was needed). */
+ * CCOLL_ENOSPC if out_cap is too small: then *out_bytes is the size that was needed, or 0 if out_cap does not
+ * even hold the header and the front index (32 + 4 * ceil(n / 5120) bytes). */
 int ccoll_szx_compress(ccoll_ctx *ctx, const float *d_in, size_t n, float abs_eb,
                        void *d_out, size_t out_cap, size_t *out_bytes);
 
@@ -155,8 +158,10 @@ int ccoll_reduce_step_op_async(ccoll_ctx *ctx, int op, const float *d_local, siz
 int ccoll_szx_decompress_static(int device, void *hip_stream, const void *d_in, size_t in_bytes,
                                 float *d_out, size_t n, unsigned long long *d_result);
 
-/* Waits for the context's stream and returns the status of the last *_async call that used
- * the context's own result slot; *bytes (may be NULL) receives its byte count. */
+/* Waits for the context's stream.  Returns the status of the *_async calls that kept their result in the
+ * context (d_result = NULL) and were enqueued since the previous ccoll_wait: CCOLL_OK if all of them went
+ * well, else the code of the latest one that failed.  *bytes (may be NULL) receives the byte count of the
+ * last such call. */
 int ccoll_wait(ccoll_ctx *ctx, size_t *bytes);
 
 const char *ccoll_strerror(int code);

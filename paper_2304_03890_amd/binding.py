@@ -201,6 +201,9 @@ class Context:
         if rc:
             raise CcollError(rc, "ccoll_szx_index")
 
+    def index_async(self, stream, n: int, result=None) -> int:
+        return self._lib.ccoll_szx_index_async(self._h, _ptr(stream), stream.numel(), n, _ptr(result))
+
     def decompress_range_indexed(self, stream, n: int, first: int, count: int, out=None) -> "torch.Tensor":
         torch = self._torch
         if out is None:

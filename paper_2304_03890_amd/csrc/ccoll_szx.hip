@@ -11,7 +11,10 @@
 //   * the wavefronts of a workgroup take consecutive chunks (a group).  Groups are handed out by a ticket
 //     counter; their byte offsets come from a single-pass decoupled look-back scan over the group sizes.  A
 //     payload is placed one turn after it was coded, when the groups in front have announced their sizes:
-//     meanwhile it stays in LDS (compress: two stages used in turns) or in the spill slot (reduce step);
+//     meanwhile it stays in LDS (a wavefront has two stages and uses them in turns); block bodies are ORed into
+//     the zeroed stage as whole aligned words, gathered four elements at a time in registers;
+//   * the reduce step (Sec. III-A.2, Eq. 2) is the coder with another source of elements: the local floats plus
+//     the incoming chunk, decoded out of a window that shares the stage with the bodies being coded;
 //   * the decompressor needs no scan between workgroups: one small kernel turns the stream's front index into
 //     chunk offsets, then every wavefront decodes a chunk out of a sliding window of its payload in LDS and
 //     writes whole 64-byte lines with streaming stores.
@@ -63,7 +66,8 @@ struct Workspace {            // lives in device memory, one per context
   u64 abort;                  // epoch of a call whose scan wait timed out
   u64 ticket[2];              // groups of chunks handed out: launches use the two counters in turns, and every
                               // launch zeroes the one the next launch will use (whatever way it ends itself)
-  u64 pad[3];
+  u64 idx_bad;                // epoch of a ccoll_szx_index call that found its stream malformed
+  u64 pad[2];
 };
 
 struct Params {
@@ -89,18 +93,11 @@ struct Params {
   u32 no_total;               // k_publish: the call reports no byte count
   u32 ticket_sel;             // which of the two ticket counters this launch draws from
   u32 spin_limit;             // polls after which a scan wait gives up
+  u32 idx_epoch;              // decompress with kept chunk offsets: the epoch of the ccoll_szx_index call that made them
+  u32 index_call;             // k_index_scan runs for ccoll_szx_index: a malformed stream is also noted in ws->idx_bad
   unsigned char* spill;       // per-wavefront slots for payloads whose place in the stream is not known yet
-  u64* trace;                 // phase time stamps of one workgroup (diagnostic builds only)
 };
 
-// Diagnostic builds (-DCCOLL_TRACE) record the shader clock at phase boundaries of the first wavefront of
-// every 256th workgroup: 8 stamps per traced workgroup.
-#ifdef CCOLL_TRACE
-#define TRACEB(ph) do { if (P.trace && (blockIdx.x & 255u) == 7u && threadIdx.x == 0 && (blockIdx.x >> 8) < 64) \
-    P.trace[(blockIdx.x >> 8) * 8 + (ph)] = (u64)clock64(); } while (0)
-#else
-#define TRACEB(ph) do {} while (0)
-#endif
 
 // ---------------------------------------------------------------------------------------------
 // small device helpers
@@ -188,6 +185,7 @@ __device__ __forceinline__ void raise_error(const Params& P, int code, u32 detai
   // codes are negative; keep the most severe (most negative) one of this epoch
   u64 word = ((u64)P.epoch << 8) | ((u64)(u32)(-code) << 4) | (u64)(detail & 15u);
   __hip_atomic_fetch_max(&P.ws->err, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (P.index_call) __hip_atomic_fetch_max(&P.ws->idx_bad, (u64)P.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- decoupled look-back over the sizes of the outgoing chunks (first wavefront, all 64 lanes) ----
@@ -503,10 +501,11 @@ __device__ __forceinline__ u32 dec_rows(int nv, int blen, const unsigned char* s
 // stages of DPP moves and selects.  All four lanes of a quad must be active.
 // One butterfly stage for two vectors (4 dwords each): k = keep ? own : partner's, where the partner is the
 // lane CTRL away.  v_cndmask with a DPP source does select and lane exchange in one instruction (the compiler
-// does not fold the two); the s_nop covers the wait states between a VALU write and a DPP read.
+// does not fold the two); the s_nop covers the wait states a DPP read needs behind a VALU write of its source (2)
+// and behind a write of EXEC (5): the compiler's hazard recogniser does not look into the block.
 //   lo[d] <- keepmask ? lo[d] : partner's hi[d]        hi[d] <- keepmask ? partner's lo[d] : hi[d]
 #define CCOLL_BUTTERFLY(PERM, KEEP_LO, KEEP_HI, o0, o1, i0, i1)                                                     \
-  asm volatile("s_nop 1\n"                                                                                            \
+  asm volatile("s_nop 4\n"                                                                                            \
                "s_mov_b64 vcc, %[klo]\n"                                                                              \
                "v_cndmask_b32_dpp %[a0], %[h0], %[l0], vcc " PERM " row_mask:0xf bank_mask:0xf\n"                     \
                "v_cndmask_b32_dpp %[a1], %[h1], %[l1], vcc " PERM " row_mask:0xf bank_mask:0xf\n"                     \
@@ -820,7 +819,6 @@ __device__ __forceinline__ void decompress_chunk(u32 c, const Params& P, const u
   fetch_window(src, 0, wend, w);
   ChunkMeta m;
   if (!parse_meta(w, payload, nbc, m)) { if (lane == 0) raise_error(P, CCOLL_ECORRUPT, 6); return; }
-  TRACEB(2);
   u32 anybad = 0;
 #pragma unroll 1
   for (int u = 0; u < kUnits; ++u) {
@@ -853,7 +851,6 @@ __device__ __forceinline__ void decompress_chunk(u32 c, const Params& P, const u
     quad_transpose(xo);
     const u64 vend = P.n < hi ? P.n : hi;                              // elements past the end of the data do not exist
     if (!rowbad) store_quad((float*)P.out, xo, ubeg + (u64)(lane & ~3u) * kE, lo, vend, P.aligned16 != 0);
-    TRACEB(3 + u);
   }
   if (__ballot(anybad != 0) != 0 && lane == 0) raise_error(P, CCOLL_ECORRUPT, 7);
 }
@@ -866,9 +863,11 @@ __global__ void __launch_bounds__(64 * kDecWaves) __attribute__((amdgpu_waves_pe
   const u32 nfull = (u32)(P.n / kChunk);
   const u32 c = P.c0 + blockIdx.x * kDecWaves + wv;
   if (c >= P.c1) return;
-  TRACEB(0);
+  if (P.idx_epoch && ld_dev(&P.ws->idx_bad) == (u64)P.idx_epoch) {     // the kept offsets come from a stream that failed its checks
+    if ((threadIdx.x & 63u) == 0) raise_error(P, CCOLL_ECORRUPT, 2);
+    return;
+  }
   const InChunk cur = locate_chunk(s, c, P, 0u);
-  TRACEB(1);
   if (!cur.ok) { if ((threadIdx.x & 63u) == 0) raise_error(P, CCOLL_ECORRUPT, 4); return; }
   if (c < nfull) decompress_chunk<true>(c, P, cur.src, cur.size, lds[wv]);
   else decompress_chunk<false>(c, P, cur.src, cur.size, lds[wv]);
@@ -1231,29 +1230,6 @@ __device__ __forceinline__ void copy_gg(unsigned char* dst, const unsigned char*
   if (lane < rest) ((u32*)(dst + 16u * n16))[lane] = ((const u32*)(src + 16u * n16))[lane];
 }
 
-// n bytes (a multiple of 4) from a 16-byte aligned global address to a 16-byte aligned LDS address.
-__device__ __forceinline__ void copy_in(unsigned char* dst, const unsigned char* src, u32 n) {
-  const u32 lane = threadIdx.x & 63u;
-  const u32 n16 = n >> 4;
-  constexpr int kBatch = 4;
-  for (u32 j0 = 0; j0 < n16; j0 += 64u * kBatch) {
-    uint4 v[kBatch];
-#pragma unroll
-    for (int i = 0; i < kBatch; ++i) {
-      const u32 j = j0 + lane + 64u * (u32)i;
-      v[i] = make_uint4(0, 0, 0, 0);
-      if (j < n16) v[i] = *(const uint4*)(src + 16u * j);
-    }
-#pragma unroll
-    for (int i = 0; i < kBatch; ++i) {
-      const u32 j = j0 + lane + 64u * (u32)i;
-      if (j < n16) *(uint4*)(dst + 16u * j) = v[i];
-    }
-  }
-  const u32 rest = (n >> 2) & 3u;
-  if (lane < rest) ((u32*)(dst + 16u * n16))[lane] = ((const u32*)(src + 16u * n16))[lane];
-}
-
 // One unit of a chunk: classify its 8 blocks, code the elements, append the bodies to the chunk's body
 // bytes (bodybase so far), mu and sizes to the metadata.  The bodies are assembled in the wavefront's LDS
 // stage; when a unit does not fit behind what is staged, the staged bytes (all but the last < 16) move on to
@@ -1373,38 +1349,6 @@ __device__ __forceinline__ void write_header(const Params& P, u64 total) {
   st_dev(&P.ws->total, total);
 }
 
-// What is still in the LDS stage of a coded chunk joins the rest in the spill slot (the payload is parked).
-template <u32 CAP>
-__device__ __forceinline__ void park_chunk(const ChunkOut& o, unsigned char* slot, EncWaveLds<CAP>& L) {
-  copy_out<false>(slot, (unsigned char*)L.meta, o.meta_len);
-  copy_out<true>(slot + kMetaMax + o.flushed, L.body, pad4(o.bodies) - o.flushed);
-}
-
-// The payload of chunk c goes to its place `off` bytes into the payload area: from the spill slot, or, if it
-// has been brought back (inlds), from the wavefront's LDS stage.
-template <u32 CAP>
-__device__ __forceinline__ void place_chunk(u32 c, const ChunkOut& o, u64 off, bool from_slot, const unsigned char* slot, const Params& P,
-                                            EncWaveLds<CAP>& L) {
-  const u32 lane = threadIdx.x & 63u;
-  unsigned char* gout = (unsigned char*)P.out;
-  const u64 front = kHeader + 4ull * P.nchunks;
-  const bool fits = front + off + o.payload <= P.out_cap;
-  if (lane == 0) {
-    if (!fits) raise_error(P, CCOLL_ENOSPC);
-    if (c + 1 == P.nchunks) write_header(P, front + off + o.payload);
-  }
-  if (!fits) return;
-  unsigned char* dst = gout + front + off;
-  const u32 nb = pad4(o.bodies);
-  if (from_slot) {
-    copy_gg(dst, slot, o.meta_len);
-    copy_gg(dst + o.meta_len, slot + kMetaMax, nb);
-  } else {
-    copy_out<false>(dst, (unsigned char*)L.meta, o.meta_len);
-    copy_out<true>(dst + o.meta_len, L.body, nb);
-  }
-}
-
 // The payload of chunk c, still in LDS stage L (and, what had outgrown it, in the spill slot), goes to its place.
 template <u32 CAP>
 __device__ __forceinline__ void place_staged(u32 c, const ChunkOut& o, u64 off, const unsigned char* slot, const Params& P,
@@ -1436,10 +1380,9 @@ struct GroupLds {
 // of it are as a rule still being coded and its place in the stream is not known, so a payload is never
 // placed in the turn it is coded in, but one turn later: by then the groups in front have announced their
 // sizes, the walk through the scan returns at once, and coding never waits for a slower workgroup.
-// Meanwhile the payload stays where it is (NS = 2: a wavefront has two LDS stages and uses them in turns) or
-// is parked in the wavefront's spill slot and brought back before it is placed (NS = 1: one LDS stage).
+// Meanwhile the payload stays where it is: a wavefront has two LDS stages and uses them in turns.
 // One barrier per turn.  slot_bytes: size of a spill slot; every wavefront has two, used in turns.
-template <int NW, u32 CAP, int NS, class Src>
+template <int NW, u32 CAP, class Src>
 __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLds<NW>& g, EncWaveLds<CAP>* Ls, u32 slot_bytes) {
   const u32 lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
   unsigned char* gout = (unsigned char*)P.out;
@@ -1452,7 +1395,7 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
 
   // bodies are ORed into the stages: they start as zeros, and every copy out of a stage leaves zeros behind
 #pragma unroll
-  for (int i = 0; i < NS; ++i)
+  for (int i = 0; i < 2; ++i)
     for (u32 j = lane; j < (CAP + 16u) / 16u; j += 64u) *(uint4*)(Ls[i].body + 16u * j) = make_uint4(0, 0, 0, 0);
   u64* ticket = &P.ws->ticket[P.ticket_sel];
   if (threadIdx.x == 0) {
@@ -1470,8 +1413,8 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
     const u32 par = turn & 1u, ts = turn % 3u, tp = (turn + 2u) % 3u;   // tp: the previous turn's sizes
     unsigned char* slot = slots + par * slot_bytes;           // this turn's
     unsigned char* pslot = slots + (par ^ 1u) * slot_bytes;   // the previous turn's
-    EncWaveLds<CAP>& L = Ls[NS == 2 ? par : 0u];
-    EncWaveLds<CAP>& Lp = Ls[NS == 2 ? par ^ 1u : 0u];        // where the previous turn's payload is (NS = 2)
+    EncWaveLds<CAP>& L = Ls[par];
+    EncWaveLds<CAP>& Lp = Ls[par ^ 1u];                       // where the previous turn's payload is
     // the next group is asked for now, it is needed after the barrier
     u64 tnext = 0;
     if (threadIdx.x == 0) tnext = __hip_atomic_fetch_add(ticket, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1479,18 +1422,8 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
     const bool have = c < P.nchunks;
     ChunkOut o; o.payload = 0; o.meta_len = 0; o.bodies = 0; o.flushed = 0;
     if (have) o = c < nfull ? encode_chunk<true, CAP>(src, c, P, gm, L, slot) : encode_chunk<false, CAP>(src, c, P, gm, L, slot);
-    // One stage: this turn's payload goes to the spill slot at once and the previous turn's payload comes back
-    // into the freed stage.  Then the first wavefront walks the scan for the previous group's place.  All of
-    // this happens while the slower wavefronts of the group still code, in front of the turn's barrier.
-    bool back = false;
-    if (NS == 1) {
-      if (have) park_chunk<CAP>(o, slot, L);
-      back = pend && phave && pad4(po.bodies) <= CAP;
-      if (back) {
-        copy_in((unsigned char*)L.meta, pslot, po.meta_len);
-        copy_in(L.body, pslot + kMetaMax, pad4(po.bodies));
-      }
-    }
+    // The first wavefront walks the scan for the previous group's place while the slower wavefronts of the
+    // group still code, in front of the turn's barrier.
     if (wv == 0 && pend) {
       u32 ptot = 0;
 #pragma unroll
@@ -1516,8 +1449,7 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
       if (phave) {
         u64 off = g.pbase[par];
         for (u32 j = 0; j < wv; ++j) off += g.size[tp][j];
-        if (NS == 2) place_staged<CAP>(pc, po, off, pslot, P, Lp);
-        else place_chunk<CAP>(pc, po, off, !back, pslot, P, L);
+        place_staged<CAP>(pc, po, off, pslot, P, Lp);
       }
     }
     pend = true; phave = have; pq = q; pc = c; po = o;
@@ -1537,8 +1469,7 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
     if (g.pres[par] == 1 && phave) {
       u64 off = g.pbase[par];
       for (u32 j = 0; j < wv; ++j) off += g.size[tp][j];
-      if (NS == 2) place_staged<CAP>(pc, po, off, slots + (par ^ 1u) * slot_bytes, P, Ls[par ^ 1u]);
-      else place_chunk<CAP>(pc, po, off, true, slots + (par ^ 1u) * slot_bytes, P, Ls[0]);
+      place_staged<CAP>(pc, po, off, slots + (par ^ 1u) * slot_bytes, P, Ls[par ^ 1u]);
     }
   }
 }
@@ -1553,7 +1484,7 @@ struct __align__(16) CompressSmem { EncWaveLds<kEncCap> wave[kEncWaves][2]; Grou
 __global__ void __launch_bounds__(64 * kEncWaves) __attribute__((amdgpu_waves_per_eu(3, 3))) k_compress(Params P) {
   __shared__ CompressSmem sm;
   SrcPlain src; src.in = (const float*)P.in; src.al = P.aligned16 != 0;
-  encode_groups<kEncWaves, kEncCap, 2>(src, P, sm.g, sm.wave[threadIdx.x >> 6], kSpillSlot);
+  encode_groups<kEncWaves, kEncCap>(src, P, sm.g, sm.wave[threadIdx.x >> 6], kSpillSlot);
 }
 
 // reduce step: 4 wavefronts per workgroup, three workgroups per compute unit; two stages per wavefront like
@@ -1571,7 +1502,7 @@ __device__ __forceinline__ void reduce_step_body(const Params& P, ReduceSmem& sm
   const u32 wv = threadIdx.x >> 6;
   SrcReduce<OP, kRedCap> src; src.local = P.local; src.al = P.aligned16 != 0; src.s = (const unsigned char*)P.cin;
   src.stage = nullptr; src.src = nullptr; src.payload = 0; src.wbase = 0; src.wlen = 0; src.wpos = 0; src.good = false;
-  encode_groups<kRedWaves, kRedCap, 2>(src, P, sm.g, sm.wave[wv], kSpillSlot);
+  encode_groups<kRedWaves, kRedCap>(src, P, sm.g, sm.wave[wv], kSpillSlot);
 }
 // one kernel per reduction, so that the sum carries nothing of the others
 __global__ void __launch_bounds__(64 * kRedWaves) __attribute__((amdgpu_waves_per_eu(CCOLL_RED_OCC, CCOLL_RED_OCC))) k_reduce_step(Params P) {
@@ -1628,6 +1559,10 @@ struct ccoll_ctx {
   u32 epoch;
   u64* host_ws;           // pinned copy of the workspace words
   u32 last_epoch;         // epoch of the last call that kept its result in the context
+  u32 waited_epoch;       // calls up to this epoch have been reported by ccoll_wait
+  u64 own_slot;           // bit i: the call of epoch (epoch - i) keeps its result in the context (not in a caller's slot)
+  u32 idx_epoch;          // epoch of the ccoll_szx_index call whose offsets are kept
+  size_t spill_waves;     // wavefronts the spill area has slots for
   bool last_total;        // that call reports a byte count
   int grid_compress, grid_decompress, grid_reduce;   // workgroups that are resident at once
   u32 ticket_sel;         // ticket counter of the next ticketed launch (0 / 1); the other one is being zeroed by the last
@@ -1635,7 +1570,6 @@ struct ccoll_ctx {
   const void* idx_ptr;    // the stream whose chunk offsets are in `offs` (ccoll_szx_index), or null
   size_t idx_bytes, idx_n;
   unsigned char* spill;   // device, one slot per wavefront of the widest ticketed launch
-  u64* trace;             // device, diagnostic builds only
 };
 
 namespace {
@@ -1653,7 +1587,7 @@ bool hip_ok(hipError_t e, const char* what) {
 int reset_workspace(ccoll_ctx* c) {
   if (!HIP_OK(hipMemsetAsync(c->ws, 0, sizeof(Workspace), c->stream))) return CCOLL_EHIP;
   if (c->stat && !HIP_OK(hipMemsetAsync(c->stat, 0, c->cap_chunks * sizeof(u64), c->stream))) return CCOLL_EHIP;
-  c->epoch = 0;
+  c->epoch = 0; c->waited_epoch = 0; c->last_epoch = 0; c->own_slot = 0; c->idx_ptr = nullptr;
   c->ticket_sel = 0;
   return CCOLL_OK;
 }
@@ -1671,10 +1605,10 @@ int prepare(ccoll_ctx* c, size_t n, Params& P) {
   memset(&P, 0, sizeof(P));
   P.n = n; P.nchunks = (u32)nchunks; P.c0 = 0; P.c1 = (u32)nchunks;
   P.epoch = ++c->epoch;
+  c->own_slot <<= 1;
   P.ws = c->ws; P.stat = c->stat; P.offs = c->offs;
   P.spin_limit = c->spin_limit;
   P.result = nullptr;
-  P.trace = c->trace;
   return CCOLL_OK;
 }
 
@@ -1685,7 +1619,7 @@ int after_launch(ccoll_ctx* c, Params& P, unsigned long long* d_result, bool rep
     P.result = (u64*)d_result; P.no_total = reports_total ? 0u : 1u;
     hipLaunchKernelGGL(k_publish, dim3(1), dim3(1), 0, c->stream, P);
   } else {
-    c->last_epoch = P.epoch; c->last_total = reports_total;
+    c->last_epoch = P.epoch; c->last_total = reports_total; c->own_slot |= 1ull;
   }
   if (!HIP_OK(hipGetLastError())) { (void)reset_workspace(c); return CCOLL_EHIP; }
   return CCOLL_OK;
@@ -1697,7 +1631,6 @@ int occupancy_grid(ccoll_ctx* c, K kernel, int threads) {
   int per_cu = 0, cus = 0;
   if (!HIP_OK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0))) return 0;
   if (!HIP_OK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device))) return 0;
-  if (const char* e = getenv("CCOLL_WG_PER_CU")) { int v = atoi(e); if (v >= 1 && v < per_cu) per_cu = v; }
   if (getenv("CCOLL_DEBUG")) fprintf(stderr, "libccoll_szx: %d workgroups of %d threads per CU, %d CUs\n", per_cu, threads, cus);
   return per_cu * cus;
 }
@@ -1721,7 +1654,7 @@ int ccoll_create(ccoll_ctx** out, int device, void* hip_stream) {
   ccoll_ctx* c = new (std::nothrow) ccoll_ctx();
   if (!c) return CCOLL_EHIP;
   c->device = device; c->stream = (hipStream_t)hip_stream; c->stat = nullptr; c->cap_chunks = 0;
-  c->ws = nullptr; c->spill = nullptr; c->spin_limit = kSpinLimit; c->idx_ptr = nullptr; c->idx_bytes = 0; c->idx_n = 0; c->host_ws = nullptr; c->trace = nullptr; c->offs = nullptr; c->last_epoch = 0; c->last_total = false;
+  c->ws = nullptr; c->spill = nullptr; c->spin_limit = kSpinLimit; c->idx_ptr = nullptr; c->idx_bytes = 0; c->idx_n = 0; c->host_ws = nullptr; c->offs = nullptr; c->last_epoch = 0; c->last_total = false; c->waited_epoch = 0; c->own_slot = 0; c->idx_epoch = 0; c->spill_waves = 0;
   if (!HIP_OK(hipMalloc((void**)&c->ws, sizeof(Workspace))) ||
       !HIP_OK(hipHostMalloc((void**)&c->host_ws, sizeof(Workspace), hipHostMallocDefault))) {
     ccoll_destroy(c); return CCOLL_EHIP;
@@ -1731,16 +1664,12 @@ int ccoll_create(ccoll_ctx** out, int device, void* hip_stream) {
   c->grid_compress = occupancy_grid(c, k_compress, 64 * kEncWaves);
   c->grid_reduce = occupancy_grid(c, k_reduce_step, 64 * kRedWaves);
   c->grid_decompress = 1;
-  {
-    const size_t wc = (size_t)(c->grid_compress > 0 ? c->grid_compress : 0) * kEncWaves;
-    const size_t wr = (size_t)(c->grid_reduce > 0 ? c->grid_reduce : 0) * kRedWaves;
-    const size_t waves = wc > wr ? wc : wr;
-    if (waves && !HIP_OK(hipMalloc((void**)&c->spill, waves * 2 * kSpillSlot))) { ccoll_destroy(c); return CCOLL_EHIP; }
-  }
   if (c->grid_compress <= 0 || c->grid_reduce <= 0 || c->grid_decompress <= 0) { ccoll_destroy(c); return CCOLL_EHIP; }
   if (reset_workspace(c) != CCOLL_OK || !HIP_OK(hipStreamSynchronize(c->stream))) { ccoll_destroy(c); return CCOLL_EHIP; }
+  const int rc = ccoll_reserve(c, (size_t)1 << 20);
+  if (rc != CCOLL_OK) { ccoll_destroy(c); return rc; }
   *out = c;
-  return ccoll_reserve(c, (size_t)1 << 20);
+  return CCOLL_OK;
 }
 
 int ccoll_reserve(ccoll_ctx* c, size_t max_n) {
@@ -1751,6 +1680,19 @@ int ccoll_reserve(ccoll_ctx* c, size_t max_n) {
   if (!g.ok) return CCOLL_EHIP;
   if (!HIP_OK(hipStreamSynchronize(c->stream))) return CCOLL_EHIP;
   c->idx_ptr = nullptr;
+  {
+    // Spill slots (two whole payloads per wavefront, for chunks that outgrow their LDS stage): one pair for
+    // every wavefront of the widest launch these sizes can lead to, at most the resident ones.
+    const size_t gc = (need + kEncWaves - 1) / kEncWaves, gr = (need + kRedWaves - 1) / kRedWaves;
+    const size_t wc = (gc < (size_t)c->grid_compress ? gc : (size_t)c->grid_compress) * kEncWaves;
+    const size_t wr = (gr < (size_t)c->grid_reduce ? gr : (size_t)c->grid_reduce) * kRedWaves;
+    const size_t waves = wc > wr ? wc : wr;
+    if (waves > c->spill_waves) {
+      if (c->spill) { (void)hipFree(c->spill); c->spill = nullptr; c->spill_waves = 0; }
+      if (!HIP_OK(hipMalloc((void**)&c->spill, waves * 2 * kSpillSlot))) return CCOLL_EHIP;
+      c->spill_waves = waves;
+    }
+  }
   if (c->stat) { (void)hipFree(c->stat); c->stat = nullptr; c->cap_chunks = 0; }
   if (c->offs) { (void)hipFree(c->offs); c->offs = nullptr; }
   if (!HIP_OK(hipMalloc((void**)&c->stat, need * sizeof(u64))) ||
@@ -1838,12 +1780,12 @@ int ccoll_szx_index_async(ccoll_ctx* c, const void* d_in, size_t in_bytes, size_
   int rc = prepare(c, n, P);
   if (rc) return rc;
   if (in_bytes < kHeader + 4ull * P.nchunks) return CCOLL_ECORRUPT;
-  P.in = d_in; P.in_bytes = in_bytes;
+  P.in = d_in; P.in_bytes = in_bytes; P.index_call = 1;
   c->idx_ptr = nullptr;
   if (n == 0) hipLaunchKernelGGL(k_check_empty, dim3(1), dim3(64), 0, c->stream, P);
   else hipLaunchKernelGGL(k_index_scan, dim3((P.nchunks + kScanTile - 1) / kScanTile), dim3(1024), 0, c->stream, P);
   rc = after_launch(c, P, d_result, false);
-  if (rc == CCOLL_OK) { c->idx_ptr = d_in; c->idx_bytes = in_bytes; c->idx_n = n; }
+  if (rc == CCOLL_OK) { c->idx_ptr = d_in; c->idx_bytes = in_bytes; c->idx_n = n; c->idx_epoch = P.epoch; }
   return rc;
 }
 
@@ -1860,6 +1802,7 @@ int ccoll_szx_decompress_range_indexed_async(ccoll_ctx* c, const void* d_in, siz
   if (rc) return rc;
   P.in = d_in; P.in_bytes = in_bytes; P.out = d_out; P.first = first; P.count = count;
   P.aligned16 = (((uintptr_t)d_out & 15) == 0);
+  P.idx_epoch = c->idx_epoch;                  // an enqueue-only index call may still turn out to have failed
   if (n == 0 || count == 0) return after_launch(c, P, d_result, false);
   P.c0 = (u32)(first / kChunk); P.c1 = (u32)((first + count + kChunk - 1) / kChunk);
   hipLaunchKernelGGL(k_decompress, dim3((P.c1 - P.c0 + kDecWaves - 1) / kDecWaves), dim3(64 * kDecWaves), 0, c->stream, P);
@@ -1965,8 +1908,12 @@ int ccoll_wait(ccoll_ctx* c, size_t* bytes) {
     return CCOLL_EHIP;
   }
   const Workspace* h = (const Workspace*)c->host_ws;
-  const bool mine = (h->err >> 8) == (u64)c->last_epoch;
+  // The error word keeps the latest failing call (and its most severe code): it is reported if that call was
+  // enqueued since the previous wait, so that an earlier failure is not hidden by later calls that went well.
+  const u64 eep = h->err >> 8, age = (u64)c->epoch - eep;
+  const bool mine = eep > (u64)c->waited_epoch && eep <= (u64)c->epoch && (age >= 64 || ((c->own_slot >> age) & 1ull));
   const int status = mine ? -(int)((h->err >> 4) & 0xfu) : 0;
+  c->waited_epoch = c->epoch;
   if (bytes) *bytes = c->last_total ? (size_t)h->total : 0;
   if (status && getenv("CCOLL_DEBUG"))
     fprintf(stderr, "libccoll_szx: device status %d (check %u)\n", status, (unsigned)(h->err & 0xfu));
@@ -1977,6 +1924,7 @@ int ccoll_wait(ccoll_ctx* c, size_t* bytes) {
 int ccoll_szx_compress(ccoll_ctx* c, const float* d_in, size_t n, float abs_eb, void* d_out, size_t out_cap,
                        size_t* out_bytes) {
   if (!out_bytes) return CCOLL_EINVAL;
+  *out_bytes = 0;
   int rc = ccoll_szx_compress_async(c, d_in, n, abs_eb, d_out, out_cap, nullptr);
   if (rc) return rc;
   return ccoll_wait(c, out_bytes);
@@ -2013,6 +1961,7 @@ int ccoll_szx_decompress_range_indexed(ccoll_ctx* c, const void* d_in, size_t in
 int ccoll_reduce_step_op(ccoll_ctx* c, int op, const float* d_local, size_t n, const void* d_cin, size_t cin_bytes,
                          float abs_eb, void* d_cout, size_t cout_cap, size_t* cout_bytes) {
   if (!cout_bytes) return CCOLL_EINVAL;
+  *cout_bytes = 0;
   int rc = ccoll_reduce_step_op_async(c, op, d_local, n, d_cin, cin_bytes, abs_eb, d_cout, cout_cap, nullptr);
   if (rc) return rc;
   return ccoll_wait(c, cout_bytes);
@@ -2023,9 +1972,6 @@ int ccoll_reduce_step(ccoll_ctx* c, const float* d_local, size_t n, const void* 
   return ccoll_reduce_step_op(c, CCOLL_OP_SUM, d_local, n, d_cin, cin_bytes, abs_eb, d_cout, cout_cap, cout_bytes);
 }
 
-#ifdef CCOLL_TRACE
-void ccoll_debug_set_trace(ccoll_ctx* c, unsigned long long* d_trace) { c->trace = (u64*)d_trace; }
-#endif
 
 const char* ccoll_strerror(int code) {
   switch (code) {

@@ -84,8 +84,9 @@ def test_ring_chunk_chain(ctx):
 
 def test_bcast_field_ranges(ctx):
     """Workload 3: one 2^28-value field compressed once, decoded as 64 ranges of 2^22 values that start in
-    the middle of chunks (32,768 blocks per range, 40 per chunk).  All 64 ranges equal the slices of the
-    full decode; a sample of them and the stream itself equal the oracle's."""
+    the middle of chunks (32,768 blocks per range, 40 per chunk).  The stream and the whole decode equal the
+    oracle's, every range equals its slice of that decode, and a sample of ranges equals the oracle's range
+    decode."""
     x = workloads.bcast_field()
     n = x.size
     eb = float(workloads.abs_bound(x, 1e-3))
@@ -93,6 +94,9 @@ def test_bcast_field_ranges(ctx):
     got = ctx.compress(dev(x), eb)
     same_bytes(got.cpu().numpy(), want, "bcast field stream")
     full = ctx.decompress(got, n)
+    full_want = ref.decompress(want, n)
+    assert torch.equal(full.view(torch.int32), dev(full_want).view(torch.int32)), "whole decode"
+    del full_want
     cnt = n // 64
     for j in range(64):
         part = ctx.decompress_range(got, n, j * cnt, cnt)
@@ -104,16 +108,58 @@ def test_bcast_field_ranges(ctx):
     assert err <= float(np.float64(np.float32(eb)))
 
 
-@pytest.mark.parametrize("noise,rel", [(0.0, 1e-2), (0.25, 1e-4), (1.0, 1e-3), (1.0, 1e-6)])
-def test_sweep_points_match_oracle(ctx, noise, rel):
-    """Workload 4, corners of the sweep: from nearly all-constant blocks to white noise under a bound so
-    tight that the chunks are larger than the coder's LDS stage (their bodies pass through the wavefront's
-    spill slot)."""
+@pytest.mark.parametrize("noise", [0.0, 0.25, 0.5, 1.0])
+def test_sweep_points_match_oracle(ctx, noise):
+    """Workload 4, all 20 points of the sweep (4 noise fractions x 5 bounds): from nearly all-constant blocks to
+    white noise under a bound so tight that every block is stored raw and the chunks are larger than the
+    coder's LDS stage (their bodies pass through the wavefront's spill slot).  Streams and decoded floats
+    equal the oracle's; at two bounds per field also the reduce step with a shifted copy of the field."""
     x = workloads.sweep_mix(noise)
-    eb = float(workloads.abs_bound(x, rel))
+    dx = dev(x)
+    for rel in (1e-2, 1e-3, 1e-4, 1e-5, 1e-6):
+        eb = float(workloads.abs_bound(x, rel))
+        want = ref.compress(x, eb)
+        got = ctx.compress(dx, eb)
+        same_bytes(got.cpu().numpy(), want, f"sweep noise={noise} rel={rel}")
+        y = ctx.decompress(got, x.size)
+        y_want = ref.decompress(want, x.size)
+        assert torch.equal(y.view(torch.int32), dev(y_want).view(torch.int32)), (noise, rel)
+        del y, y_want
+        if rel in (1e-3, 1e-5):
+            local = np.roll(x, 3)
+            r_want = ref.reduce_step(local, want, eb)
+            r_got = ctx.reduce_step(dev(local), got, eb)
+            same_bytes(r_got.cpu().numpy(), r_want, f"sweep reduce noise={noise} rel={rel}")
+
+
+def test_more_than_2_to_30_values(ctx):
+    """The documented limit is n <= 2^31: one stream of 2^30 + 3 chunks + 77 values (4.3 GB of floats, 209,719
+    chunks, 26 tiles of the index scan, offsets beyond 2^32 in a noisy part) against the oracle: stream bytes,
+    decoded floats of both ends and of a range across the 2^32-byte mark of the input."""
+    n = (1 << 30) + 5120 * 3 + 77
+    base = workloads.vector_1d(1 << 22)
+    noisy = (base + np.random.default_rng(3).standard_normal(base.size).astype(np.float32) * 0.05).astype(np.float32)
+    x = np.empty(n, np.float32)
+    for i0 in range(0, n, base.size):                      # smooth and noisy pieces in turns: CR about 1.65
+        m = min(base.size, n - i0)
+        x[i0:i0 + m] = (noisy if (i0 // base.size) % 2 else base)[:m]
+    eb = float(workloads.abs_bound(base, 1e-5))
+    ctx.reserve(n)
+    dx = dev(x)
+    got = ctx.compress(dx, eb)
     want = ref.compress(x, eb)
-    got = ctx.compress(dev(x), eb)
-    same_bytes(got.cpu().numpy(), want, f"sweep noise={noise} rel={rel}")
-    y = ctx.decompress(got, x.size)
-    y_want = ref.decompress(want, x.size)
-    assert torch.equal(y.view(torch.int32), dev(y_want).view(torch.int32))
+    assert got.numel() == want.size
+    assert got.numel() > (1 << 31), "the stream should be longer than 2^31 bytes for this test to mean much"
+    step = 1 << 28
+    for o in range(0, want.size, step):                    # compare on the device, piece by piece
+        assert torch.equal(got[o:o + step], dev(want[o:o + step])), ("stream bytes from", o)
+    y = ctx.decompress(got, n)
+    err = 0.0
+    for o in range(0, n, step):
+        err = max(err, (y[o:o + step].double() - dx[o:o + step].double()).abs().max().item())
+    assert err <= float(np.float64(np.float32(eb)))
+    for first, count in ((0, 5120 * 2 + 128), (n - 5120 - 77, 5120 + 77), ((1 << 30) - 128 * 50, 128 * 100)):
+        part = ref.decompress_range(want, first, count)
+        assert np.array_equal(y[first:first + count].cpu().numpy().view(np.uint32), part.view(np.uint32)), first
+        r = ctx.decompress_range(got, n, first, count)
+        assert np.array_equal(r.cpu().numpy().view(np.uint32), part.view(np.uint32)), first
