@@ -8,7 +8,14 @@ calls on one stream.  `value` is uncompressed float32 bytes handled per second b
 compression ratio and the roofline of the slowest call are in the same JSON line, next to the durations of
 the same calls launched 20 times in a row.  The CPU oracle is timed beside it on a bounded sample.
 
+Besides the headline line (the 512^3 field at relative bound 1e-3) the same JSON object carries, unless
+--no-extras is given, the other workloads of the benchmark spec: `ring8` (the per-rank compute of a compressed ring
+reduce-scatter of 8 simulated ranges held in one GPU's memory: 8 x (1 compress + 7 reduce steps) on chunks of
+17,958,405 values), `bcast64` (one 2^28-value field compressed once and decoded as 64 ranges) and `sweep`
+(20 points of noise fraction x bound).
+
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload field512|vector|field256] [--rel-eb 1e-3]
+                       [--no-extras] [--cpu-sample N]
 """
 from __future__ import annotations
 
@@ -49,21 +56,67 @@ def time_kernel(torch, fn, reps: int) -> float:
     return e0.elapsed_time(e1) / reps
 
 
+def _cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(x, eb, sample_elems: int):
-    """The oracle as it stands, single thread, on the first `sample_elems` values of the same input."""
+    """The oracle as it stands on the first `sample_elems` values of the same input.  Primary figure: one thread
+    pinned to one core, median of three runs per call (the protocol of the paper's single-thread Table I).
+    Secondary, labelled: the same unchanged oracle functions called from a thread pool on independent ranges of
+    chunks, one per host core this process may use."""
+    import statistics
+    from concurrent.futures import ThreadPoolExecutor
     import numpy as np
     from oracle import ref
     xs = np.ascontiguousarray(x[:sample_elems])
-    t0 = time.perf_counter(); s = ref.compress(xs, eb); t1 = time.perf_counter()
-    y = ref.decompress(s, xs.size); t2 = time.perf_counter()
-    r = ref.reduce_step(xs, s, eb); t3 = time.perf_counter()
+    loc = np.roll(xs, 1)
+    allowed = sorted(os.sched_getaffinity(0))
+    core = allowed[len(allowed) // 2]
+    os.sched_setaffinity(0, {core})
+    try:
+        s = ref.compress(xs, eb)
+        tc, td, tr = [], [], []
+        for _ in range(3):
+            t0 = time.perf_counter(); s = ref.compress(xs, eb); t1 = time.perf_counter()
+            y = ref.decompress(s, xs.size); t2 = time.perf_counter()
+            r = ref.reduce_step(loc, s, eb); t3 = time.perf_counter()
+            tc.append(t1 - t0); td.append(t2 - t1); tr.append(t3 - t2)
+            del y, r
+    finally:
+        os.sched_setaffinity(0, set(allowed))
+    mc, md, mr = statistics.median(tc), statistics.median(td), statistics.median(tr)
     gb = 4.0 * xs.size / 1e9
-    del y, r
+    # all host cores: the input cut into ranges of whole chunks, one oracle call per range and thread
+    nthreads = max(1, min(len(allowed), 16))
+    per = -(-(xs.size // 5120 + 1) // nthreads) * 5120
+    pieces = [(i, min(xs.size, i + per)) for i in range(0, xs.size, per)]
+
+    def one(rng):
+        a, b = rng
+        st = ref.compress(xs[a:b], eb)
+        yy = ref.decompress(st, b - a)
+        rr = ref.reduce_step(loc[a:b], st, eb)
+        return yy.size + rr.size
+
+    with ThreadPoolExecutor(nthreads) as ex:
+        list(ex.map(one, pieces[:nthreads]))           # warm
+        t0 = time.perf_counter(); list(ex.map(one, pieces)); t1 = time.perf_counter()
     return {
-        "value": round(3 * gb / (t3 - t0), 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-        "sample": f"first {xs.size} values of the same field: compress + decompress + reduce_step, one run each",
-        "compress_GBps": round(gb / (t1 - t0), 4), "decompress_GBps": round(gb / (t2 - t1), 4),
-        "reduce_step_GBps": round(gb / (t3 - t2), 4),
+        "value": round(3 * gb / (mc + md + mr), 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"first {xs.size} values of the same field: compress + decompress + reduce_step, one thread pinned to "
+                  f"core {core}, median of 3 runs per call",
+        "compress_GBps": round(gb / mc, 4), "decompress_GBps": round(gb / md, 4), "reduce_step_GBps": round(gb / mr, 4),
+        "cpu_model": _cpu_model(), "host_cores_total": os.cpu_count(), "host_cores_usable": len(allowed),
+        "all_cores": {"value": round(3 * gb / (t1 - t0), 4), "unit": "GB/s", "threads": nthreads,
+                      "note": "secondary: the unchanged oracle called on independent ranges of chunks from a thread pool"},
     }
 
 
@@ -137,6 +190,165 @@ def run_table(path, pkg, torch, workloads):
     return rows
 
 
+def _events(torch, k):
+    return [torch.cuda.Event(enable_timing=True) for _ in range(k)]
+
+
+def bench_ring8(pkg, torch, workloads):
+    """Workload 2: ring reduce-scatter of P = 8 simulated ranks (Sec. III-A.2, Fig. 4, Eq. 2) in one GPU's memory.
+    The chunk that rank k starts with travels the ring: compressed once, then reduced (decompress + add the local
+    chunk + recompress) by the seven other ranks; a "send" is a pointer hand-off.  All eight chains run round by
+    round as in the collective: 8 compress calls, then 7 rounds of 8 reduce steps."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    P, n, eb = 8, 143_667_240 // 8, float(np.float32(1e-5))
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(8) as ex:          # data[r][k]: chunk k of rank r's gradient-like vector
+        host = list(ex.map(lambda i: workloads.gradient_like(n, seed=workloads.SEED_GRAD + 97 * (i // P) + (i % P)), range(P * P)))
+    data = [[torch.from_numpy(host[r * P + k]).cuda() for k in range(P)] for r in range(P)]
+    del host
+    gen_s = time.perf_counter() - t0
+    ctx = pkg.Context(0, reserve_n=n)
+    cap = pkg.max_compressed_bytes(n)
+    S = [[torch.empty(cap, dtype=torch.uint8, device="cuda") for _ in range(2)] for _ in range(P)]
+
+    def run(ev=None):
+        i = 0
+        for k in range(P):
+            if ev: ev[i].record()
+            assert ctx.compress_async(data[k][k], eb, S[k][0]) == 0
+            i += 1
+        for j in range(1, P):
+            for k in range(P):
+                if ev: ev[i].record()
+                assert ctx.reduce_step_async(data[(k + j) % P][k], S[k][(j - 1) & 1], eb, S[k][j & 1], cin_bytes=cap) == 0
+                i += 1
+        if ev: ev[i].record()
+
+    run(); st, _ = ctx.wait(); assert st == 0, st
+    run(); torch.cuda.synchronize()
+    reps = 3
+    tot, tcomp, tred = [], [], []
+    for _ in range(reps):
+        ev = _events(torch, P * P + 1)
+        run(ev); torch.cuda.synchronize()
+        d = [ev[i].elapsed_time(ev[i + 1]) for i in range(P * P)]
+        tot.append(ev[0].elapsed_time(ev[-1])); tcomp.append(sum(d[:P]) / P); tred.append(sum(d[P:]) / (P * (P - 1)))
+    ms_tot, ms_c, ms_r = min(tot), min(tcomp), min(tred)
+    # accuracy of the reduced chunks against the float64 sum, and sizes
+    fin = (P - 1) & 1
+    worst, inside, count, out_bytes = 0.0, 0, 0, 0
+    bound = (2.0 / 3.0) * (P ** 0.5) * eb
+    y = torch.empty(n, dtype=torch.float32, device="cuda")
+    for k in range(P):
+        assert ctx.decompress_async(S[k][fin], n, y, in_bytes=cap) == 0
+        st, _ = ctx.wait(); assert st == 0, st
+        exact = torch.zeros(n, dtype=torch.float64, device="cuda")
+        for r in range(P):
+            exact += data[r][k].double()
+        err = (y.double() - exact).abs()
+        worst = max(worst, err.max().item()); inside += int((err <= bound).sum().item()); count += n
+        out_bytes += int(S[k][fin][24:32].view(torch.int64).item())
+        del exact, err
+    first_bytes = int(S[0][0][24:32].view(torch.int64).item())
+    ctx.close()
+    gb = 4.0 * n / 1e9
+    return {
+        "workload": "P=8 simulated ranks x 143,667,240 gradient-like values (Laplace(0,1e-3), 20% zeros), abs eb 1e-5; "
+                    "8 chains of 1 compress + 7 reduce steps on chunks of 17,958,405 values",
+        "n_per_call": n, "calls": P * P, "ms_total": round(ms_tot, 3),
+        "aggregate_GBps": round(P * P * gb / (ms_tot * 1e-3), 1),
+        "compress_ms": round(ms_c, 4), "compress_GBps": round(gb / (ms_c * 1e-3), 1),
+        "reduce_step_ms": round(ms_r, 4), "reduce_step_GBps": round(gb / (ms_r * 1e-3), 1),
+        "CR_first_round": round(4.0 * n / first_bytes, 3), "CR_reduced": round(4.0 * n * P / out_bytes, 3),
+        "max_abs_err_over_P_eb": round(worst / (P * eb), 4), "max_abs_err_over_eb": round(worst / eb, 3),
+        "frac_within_two_thirds_sqrtP_eb": round(inside / count, 5), "input_generation_s": round(gen_s, 1),
+    }
+
+
+def bench_bcast64(pkg, torch, workloads):
+    """Workload 3: one 2^28-value field compressed once (the root of a C-Bcast / C-Scatter), decoded as 64 ranges
+    of 2^22 values that start in the middle of chunks: 64 plain range calls, 64 calls over a kept index, and one
+    call for all 64 ranges."""
+    x = workloads.bcast_field()
+    n = x.size
+    eb = float(workloads.abs_bound(x, 1e-3))
+    dx = torch.from_numpy(x).cuda()
+    del x
+    ctx = pkg.Context(0, reserve_n=n)
+    cap = pkg.max_compressed_bytes(n)
+    s = torch.empty(cap, dtype=torch.uint8, device="cuda")
+    y = torch.empty(n, dtype=torch.float32, device="cuda")
+    assert ctx.compress_async(dx, eb, s) == 0
+    st, nb = ctx.wait(); assert st == 0, st
+    cnt = n // 64
+    firsts, counts = [j * cnt for j in range(64)], [cnt] * 64
+    outs = [y[j * cnt:(j + 1) * cnt] for j in range(64)]
+    ms_c = time_kernel(torch, lambda: ctx.compress_async(dx, eb, s), 10)
+    ms_full = time_kernel(torch, lambda: ctx.decompress_async(s, n, y, in_bytes=nb), 10)
+
+    def plain():
+        for j in range(64):
+            ctx.decompress_range_async(s[:nb], n, firsts[j], cnt, outs[j])
+
+    def indexed():
+        for j in range(64):
+            ctx.decompress_range_indexed_async(s[:nb], n, firsts[j], cnt, outs[j])
+
+    ms_plain = time_kernel(torch, plain, 5)
+    ctx.index(s[:nb], n)
+    ms_idx = time_kernel(torch, indexed, 5)
+    ms_batch = time_kernel(torch, lambda: ctx.decompress_ranges_async(s[:nb], n, firsts, counts, outs), 10)
+    st, _ = ctx.wait(); assert st == 0, st
+    err = (y.double() - dx.double()).abs().max().item()
+    ctx.close()
+    gb = 4.0 * n / 1e9
+    return {
+        "workload": "3D float32 field 1024x512x512 (blobs + 8 sinusoidal modes), rel eb 1e-3, 64 ranges of 2^22 values",
+        "n": n, "CR": round(4.0 * n / nb, 3), "max_abs_err_over_eb": round(err / eb, 4),
+        "compress_ms": round(ms_c, 4), "compress_GBps": round(gb / (ms_c * 1e-3), 1),
+        "decompress_full_ms": round(ms_full, 4), "decompress_full_GBps": round(gb / (ms_full * 1e-3), 1),
+        "ranges64_plain_calls_ms": round(ms_plain, 4), "ranges64_indexed_calls_ms": round(ms_idx, 4),
+        "ranges64_one_call_ms": round(ms_batch, 4), "ranges64_one_call_GBps": round(gb / (ms_batch * 1e-3), 1),
+    }
+
+
+def bench_sweep(pkg, torch, workloads):
+    """Workload 4: noise fraction {0, .25, .5, 1} x relative bound {1e-2 .. 1e-6} on 2^27 values."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    fracs = (0.0, 0.25, 0.5, 1.0)
+    with ThreadPoolExecutor(4) as ex:
+        fields = list(ex.map(workloads.sweep_mix, fracs))
+    n = fields[0].size
+    ctx = pkg.Context(0, reserve_n=n)
+    cap = pkg.max_compressed_bytes(n)
+    s1 = torch.empty(cap, dtype=torch.uint8, device="cuda"); s2 = torch.empty(cap, dtype=torch.uint8, device="cuda")
+    y = torch.empty(n, dtype=torch.float32, device="cuda")
+    rows = []
+    gb = 4.0 * n / 1e9
+    for frac, x in zip(fracs, fields):
+        dx = torch.from_numpy(x).cuda(); dl = torch.roll(dx, 1)
+        for rel in (1e-2, 1e-3, 1e-4, 1e-5, 1e-6):
+            eb = float(workloads.abs_bound(x, rel))
+            assert ctx.compress_async(dx, eb, s1) == 0
+            st, cb = ctx.wait(); assert st == 0, st
+            tc = time_kernel(torch, lambda: ctx.compress_async(dx, eb, s1), 8)
+            td = time_kernel(torch, lambda: ctx.decompress_async(s1, n, y, in_bytes=cb), 8)
+            tr = time_kernel(torch, lambda: ctx.reduce_step_async(dl, s1, eb, s2, cin_bytes=cb), 8)
+            st, rb = ctx.wait(); assert st == 0, st
+            ctx.decompress_async(s1, n, y, in_bytes=cb); st, _ = ctx.wait(); assert st == 0, st
+            err = (y.double() - dx.double()).abs().max().item() / eb
+            const, raw = stream_stats(s1[:cb].cpu().numpy(), n)
+            rows.append({"noise": frac, "rel_eb": rel, "CR": round(4.0 * n / cb, 3), "const_blocks": round(const, 4),
+                         "raw_blocks": round(raw, 4), "compress_GBps": round(gb / tc * 1e3, 1),
+                         "decompress_GBps": round(gb / td * 1e3, 1), "reduce_step_GBps": round(gb / tr * 1e3, 1),
+                         "max_abs_err_over_eb": round(err, 4)})
+        del dx, dl
+    ctx.close()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -146,6 +358,7 @@ def main():
     ap.add_argument("--rel-eb", type=float, default=1e-3)
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="elements the oracle is timed on (0 = skip)")
     ap.add_argument("--table", default=None, help="also run all workloads and bounds and write a markdown table to this path")
+    ap.add_argument("--no-extras", action="store_true", help="only the headline workload (no ring8 / bcast64 / sweep keys)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -248,14 +461,19 @@ def main():
             tr = json.load(f)
         if tr.get("workload") == args.workload and abs(tr.get("rel_eb", 0) - args.rel_eb) < 1e-12:
             line["roofline"]["traffic"] = tr["kernels"].get(dom)
+            line["roofline"]["traffic_measured_at_commit"] = tr.get("commit")
     except (OSError, ValueError):
         pass
     if args.cpu_sample > 0:
         line["cpu_baseline"] = cpu_baseline(x, eb, min(n, args.cpu_sample))
     ctx.close()
+    del dx, dlocal, stream, stream2, y
+    torch.cuda.empty_cache()
+    if not args.no_extras:
+        for key, fn in (("ring8", bench_ring8), ("bcast64", bench_bcast64), ("sweep", bench_sweep)):
+            line[key] = fn(pkg, torch, workloads)
+            torch.cuda.empty_cache()
     if args.table:
-        del dx, dlocal, stream, stream2, y
-        torch.cuda.empty_cache()
         run_table(args.table, pkg, torch, workloads)
     print(json.dumps(line))
 

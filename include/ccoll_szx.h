@@ -103,6 +103,15 @@ int ccoll_szx_index(ccoll_ctx *ctx, const void *d_in, size_t in_bytes, size_t n)
 int ccoll_szx_decompress_range_indexed(ccoll_ctx *ctx, const void *d_in, size_t in_bytes, size_t n,
                                        size_t first_elem, size_t count, float *d_out);
 
+/* Many ranges of one stream at once (C-Scatter, Sec. III-A.1 and IV-C: the root compresses once, every
+ * receiver's part is decoded from the same stream): the header and the front index are checked once and the
+ * ranges are decoded by one launch per CCOLL_MAX_RANGES_PER_LAUNCH ranges.  first_elem[r] (multiples of 128),
+ * count[r] and d_out[r] (device pointers, 4-byte aligned) are HOST arrays of nranges entries, read before the
+ * call returns; d_out[r][0] receives element first_elem[r].  Ranges may overlap or leave gaps. */
+#define CCOLL_MAX_RANGES_PER_LAUNCH 64
+int ccoll_szx_decompress_ranges(ccoll_ctx *ctx, const void *d_in, size_t in_bytes, size_t n, size_t nranges,
+                                const size_t *first_elem, const size_t *count, float *const *d_out);
+
 /* One round of the compressed ring reduce-scatter (Sec. III-A.2, Eq. 2):
  * cout = compress(local + decompress(cin), abs_eb), float32 round-to-nearest sum.
  * n = element count of d_local and of the stream in d_cin. */
@@ -130,6 +139,9 @@ int ccoll_szx_decompress_async(ccoll_ctx *ctx, const void *d_in, size_t in_bytes
 int ccoll_szx_decompress_range_async(ccoll_ctx *ctx, const void *d_in, size_t in_bytes, size_t n,
                                      size_t first_elem, size_t count, float *d_out,
                                      unsigned long long *d_result);
+int ccoll_szx_decompress_ranges_async(ccoll_ctx *ctx, const void *d_in, size_t in_bytes, size_t n, size_t nranges,
+                                      const size_t *first_elem, const size_t *count, float *const *d_out,
+                                      unsigned long long *d_result);
 int ccoll_szx_index_async(ccoll_ctx *ctx, const void *d_in, size_t in_bytes, size_t n, unsigned long long *d_result);
 int ccoll_szx_decompress_range_indexed_async(ccoll_ctx *ctx, const void *d_in, size_t in_bytes, size_t n,
                                              size_t first_elem, size_t count, float *d_out,

@@ -29,6 +29,13 @@ _SIGNATURES = {
     "ccoll_reduce_step": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                          ctypes.c_size_t, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t,
                                          ctypes.POINTER(ctypes.c_size_t)]),
+    "ccoll_szx_decompress_ranges": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t,
+                                                   ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t),
+                                                   ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_void_p)]),
+    "ccoll_szx_decompress_ranges_async": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t,
+                                                         ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t),
+                                                         ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_void_p),
+                                                         ctypes.c_void_p]),
     "ccoll_szx_index": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t]),
     "ccoll_szx_index_async": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t,
                                              ctypes.c_void_p]),
@@ -194,6 +201,29 @@ class Context:
         if rc:
             raise CcollError(rc, "ccoll_szx_decompress_range")
         return out
+
+    @staticmethod
+    def _range_arrays(firsts, counts, outs):
+        k = len(firsts)
+        return ((ctypes.c_size_t * k)(*firsts), (ctypes.c_size_t * k)(*counts),
+                (ctypes.c_void_p * k)(*[o.data_ptr() for o in outs]))
+
+    def decompress_ranges(self, stream, n: int, firsts, counts, outs=None):
+        """ccoll_szx_decompress_ranges: many ranges of one stream in one call; returns the list of outputs."""
+        torch = self._torch
+        if outs is None:
+            outs = [torch.empty(c, dtype=torch.float32, device=stream.device) for c in counts]
+        f, c, o = self._range_arrays(firsts, counts, outs)
+        rc = self._lib.ccoll_szx_decompress_ranges(self._h, _ptr(stream), stream.numel(), n, len(firsts), f, c, o)
+        if rc:
+            raise CcollError(rc, "ccoll_szx_decompress_ranges")
+        return outs
+
+    def decompress_ranges_async(self, stream, n: int, firsts, counts, outs, result=None, in_bytes: int | None = None) -> int:
+        f, c, o = self._range_arrays(firsts, counts, outs)
+        return self._lib.ccoll_szx_decompress_ranges_async(self._h, _ptr(stream),
+                                                           stream.numel() if in_bytes is None else in_bytes, n,
+                                                           len(firsts), f, c, o, _ptr(result))
 
     def index(self, stream, n: int):
         """ccoll_szx_index: checks header and front index once; decompress_range_indexed then skips that."""

@@ -873,6 +873,34 @@ __global__ void __launch_bounds__(64 * kDecWaves) __attribute__((amdgpu_waves_pe
   else decompress_chunk<false>(c, P, cur.src, cur.size, lds[wv]);
 }
 
+// Many ranges of one stream in one launch (the receivers' parts of a scattered or broadcast stream, Sec. IV-C):
+// a workgroup looks up which range it works for in a small table that travels with the kernel arguments.
+constexpr int kMaxRanges = CCOLL_MAX_RANGES_PER_LAUNCH;
+struct RangeTable {
+  u64 first[kMaxRanges], count[kMaxRanges];
+  float* out[kMaxRanges];
+  u32 wg_end[kMaxRanges];                            // workgroups of ranges 0..r, running total
+  u32 nranges;
+};
+__global__ void __launch_bounds__(64 * kDecWaves) __attribute__((amdgpu_waves_per_eu(4, 4))) k_decompress_ranges(Params P, RangeTable T) {
+  __shared__ __align__(16) unsigned char lds[kDecWaves][kRegion];
+  const unsigned char* s = (const unsigned char*)P.in;
+  const u32 wv = threadIdx.x >> 6;
+  u32 lo = 0, hi = T.nranges - 1u;                   // first range whose running total exceeds the workgroup's number
+  while (lo < hi) { const u32 mid = (lo + hi) >> 1; if (blockIdx.x >= T.wg_end[mid]) lo = mid + 1u; else hi = mid; }
+  const u32 r = lo, wg0 = r ? T.wg_end[r - 1u] : 0u;
+  Params Q = P;
+  Q.first = T.first[r]; Q.count = T.count[r]; Q.out = T.out[r];
+  Q.aligned16 = (((uintptr_t)T.out[r]) & 15u) == 0;
+  const u32 c1 = (u32)((Q.first + Q.count + kChunk - 1) / kChunk);
+  const u32 c = (u32)(Q.first / kChunk) + (blockIdx.x - wg0) * kDecWaves + wv;
+  if (c >= c1) return;
+  const InChunk cur = locate_chunk(s, c, Q, 0u);
+  if (!cur.ok) { if ((threadIdx.x & 63u) == 0) raise_error(Q, CCOLL_ECORRUPT, 4); return; }
+  if (c < (u32)(Q.n / kChunk)) decompress_chunk<true>(c, Q, cur.src, cur.size, lds[wv]);
+  else decompress_chunk<false>(c, Q, cur.src, cur.size, lds[wv]);
+}
+
 // ---------------------------------------------------------------------------------------------
 // compress and reduce step: one wavefront per chunk
 // ---------------------------------------------------------------------------------------------
@@ -1809,6 +1837,46 @@ int ccoll_szx_decompress_range_indexed_async(ccoll_ctx* c, const void* d_in, siz
   return after_launch(c, P, d_result, false);
 }
 
+int ccoll_szx_decompress_ranges_async(ccoll_ctx* c, const void* d_in, size_t in_bytes, size_t n, size_t nranges,
+                                      const size_t* first, const size_t* count, float* const* d_out,
+                                      unsigned long long* d_result) {
+  if (!c || !d_in || n > ((size_t)1 << 31) || ((uintptr_t)d_in & 3)) return CCOLL_EINVAL;
+  if (nranges && (!first || !count || !d_out)) return CCOLL_EINVAL;
+  for (size_t r = 0; r < nranges; ++r) {
+    if ((!d_out[r] && count[r]) || ((uintptr_t)d_out[r] & 3) || (first[r] % kBlock)) return CCOLL_EINVAL;
+    if (first[r] > n || count[r] > n - first[r]) return CCOLL_EINVAL;
+  }
+  DeviceGuard g(c->device);
+  if (!g.ok) return CCOLL_EHIP;
+  Params P;
+  int rc = prepare(c, n, P);
+  if (rc) return rc;
+  if (in_bytes < kHeader + 4ull * P.nchunks) return CCOLL_ECORRUPT;
+  P.in = d_in; P.in_bytes = in_bytes;
+  if (n == 0) {
+    hipLaunchKernelGGL(k_check_empty, dim3(1), dim3(64), 0, c->stream, P);
+    return after_launch(c, P, d_result, false);
+  }
+  c->idx_ptr = nullptr;                        // the offsets in the context are about to be this stream's
+  hipLaunchKernelGGL(k_index_scan, dim3((P.nchunks + kScanTile - 1) / kScanTile), dim3(1024), 0, c->stream, P);
+  for (size_t r0 = 0; r0 < nranges; r0 += kMaxRanges) {      // up to 64 ranges per launch: the table is a kernel argument
+    RangeTable T;
+    memset(&T, 0, sizeof(T));
+    u32 wgs = 0, k = 0;
+    for (size_t r = r0; r < nranges && k < (u32)kMaxRanges; ++r, ++k) {
+      T.first[k] = first[r]; T.count[k] = count[r]; T.out[k] = d_out[r];
+      if (count[r]) {
+        const u64 c0 = first[r] / kChunk, c1 = (first[r] + count[r] + kChunk - 1) / kChunk;
+        wgs += (u32)((c1 - c0 + kDecWaves - 1) / kDecWaves);
+      }
+      T.wg_end[k] = wgs;
+    }
+    T.nranges = k;
+    if (wgs) hipLaunchKernelGGL(k_decompress_ranges, dim3(wgs), dim3(64 * kDecWaves), 0, c->stream, P, T);
+  }
+  return after_launch(c, P, d_result, false);
+}
+
 int ccoll_szx_decompress_async(ccoll_ctx* c, const void* d_in, size_t in_bytes, float* d_out, size_t n,
                                unsigned long long* d_result) {
   return ccoll_szx_decompress_range_async(c, d_in, in_bytes, n, 0, n, d_out, d_result);
@@ -1939,6 +2007,13 @@ int ccoll_szx_decompress(ccoll_ctx* c, const void* d_in, size_t in_bytes, float*
 int ccoll_szx_decompress_range(ccoll_ctx* c, const void* d_in, size_t in_bytes, size_t n, size_t first, size_t count,
                                float* d_out) {
   int rc = ccoll_szx_decompress_range_async(c, d_in, in_bytes, n, first, count, d_out, nullptr);
+  if (rc) return rc;
+  return ccoll_wait(c, nullptr);
+}
+
+int ccoll_szx_decompress_ranges(ccoll_ctx* c, const void* d_in, size_t in_bytes, size_t n, size_t nranges,
+                                const size_t* first, const size_t* count, float* const* d_out) {
+  int rc = ccoll_szx_decompress_ranges_async(c, d_in, in_bytes, n, nranges, first, count, d_out, nullptr);
   if (rc) return rc;
   return ccoll_wait(c, nullptr);
 }

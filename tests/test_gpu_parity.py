@@ -501,6 +501,53 @@ def test_indexed_range_decode(ctx):
     assert np.array_equal(y2.view(np.uint32), full[128:384].view(np.uint32))
 
 
+def test_many_ranges_in_one_call(ctx):
+    """ccoll_szx_decompress_ranges: 64 equal ranges that start in the middle of chunks, then 150 ranges of mixed
+    sizes (three launches: a launch takes 64), overlapping, empty, out of order, into outputs at addresses that
+    are multiples of 4 only; every range equals the oracle's range decode; bad arguments and a corrupt stream
+    are refused."""
+    import paper_2304_03890_amd as pkg
+    x = workloads.blob_field((48, 96, 128), seed=21).ravel()
+    n = x.size
+    eb = float(workloads.abs_bound(x, 1e-3))
+    want = ref.compress(x, eb)
+    full = ref.decompress(want, n)
+    s = dev(want)
+    cnt = n // 64
+    assert cnt % 128 == 0 and cnt % 5120 != 0
+    outs = ctx.decompress_ranges(s, n, [j * cnt for j in range(64)], [cnt] * 64)
+    got = torch.cat(outs).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), full.view(np.uint32))
+    rng = np.random.default_rng(12)
+    firsts, counts = [], []
+    for j in range(150):
+        f = int(rng.integers(0, n // 128 + 1)) * 128
+        c = 0 if j % 17 == 0 else int(rng.integers(1, min(n - f, 40000) + 1)) if f < n else 0
+        firsts.append(f); counts.append(c)
+    big = torch.zeros(sum(counts) + 150 * 3 + 8, dtype=torch.float32, device="cuda")
+    views, pos = [], 1
+    for c in counts:
+        views.append(big[pos:pos + c]); pos += c + 3
+    res = torch.full((2,), -5, dtype=torch.int64, device="cuda")
+    assert ctx.decompress_ranges_async(s, n, firsts, counts, views, res) == 0
+    torch.cuda.synchronize()
+    assert res.tolist() == [0, 0]
+    for f, c, v in zip(firsts, counts, views):
+        assert np.array_equal(v.cpu().numpy().view(np.uint32), full[f:f + c].view(np.uint32)), (f, c)
+    assert float(big.abs().sum()) == pytest.approx(sum(float(np.abs(full[f:f + c]).sum(dtype=np.float64)) for f, c in zip(firsts, counts)), rel=1e-4)
+    with pytest.raises(pkg.CcollError) as e:
+        ctx.decompress_ranges(s, n, [64], [128])                 # not a multiple of the block size
+    assert e.value.code == pkg.EINVAL
+    with pytest.raises(pkg.CcollError) as e:
+        ctx.decompress_ranges(s, n, [128], [n])                  # beyond the end
+    assert e.value.code == pkg.EINVAL
+    bad = want.copy(); bad[-5] ^= 0xff; bad[40] ^= 0x10
+    with pytest.raises(pkg.CcollError) as e:
+        ctx.decompress_ranges(dev(bad), n, [0, 128 * 7], [n, 128])
+    assert e.value.code == pkg.ECORRUPT
+    assert ctx.decompress_ranges(s, n, [], []) == []
+
+
 def test_two_contexts_on_two_streams():
     """Two contexts, each on its own stream, used in turns without waiting: the scan state, tickets and spill
     slots belong to a context, so the calls do not disturb each other."""
