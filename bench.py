@@ -11,11 +11,12 @@ the same calls launched 20 times in a row.  The CPU oracle is timed beside it on
 Besides the headline line (the 512^3 field at relative bound 1e-3) the same JSON object carries, unless
 --no-extras is given, the other workloads of the benchmark spec: `ring8` (the per-rank compute of a compressed ring
 reduce-scatter of 8 simulated ranges held in one GPU's memory: 8 x (1 compress + 7 reduce steps) on chunks of
-17,958,405 values), `bcast64` (one 2^28-value field compressed once and decoded as 64 ranges) and `sweep`
-(20 points of noise fraction x bound).
+17,958,405 values), `bcast64` (one 2^28-value field compressed once and decoded as 64 ranges), `sweep`
+(20 points of noise fraction x bound) and `pipe` (the headline field written, forwarded and decoded piece by piece
+on two HIP streams).
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload field512|vector|field256] [--rel-eb 1e-3]
-                       [--no-extras] [--cpu-sample N]
+                       [--no-extras | --extras pipe,ring8,bcast64,sweep] [--cpu-sample N]
 """
 from __future__ import annotations
 
@@ -313,6 +314,64 @@ def bench_bcast64(pkg, torch, workloads):
     }
 
 
+def bench_pipe(pkg, torch, workloads, x, eb, pieces: int = 8):
+    """PIPE-SZx on one GPU (Sec. III-E.2): the headline field written as one stream in `pieces` launches on one
+    HIP stream while a second HIP stream forwards (device copy: the transport's stand-in) and decodes every piece
+    that is final.  Compared with the same three stages one after the other on one stream."""
+    n = x.size
+    nchunks = -(-n // 5120)
+    per = -(-nchunks // pieces // 12) * 12
+    bounds = list(range(0, nchunks, per)) + [nchunks]
+    k = len(bounds) - 1
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    ca, cb = pkg.Context(0, stream=sa, reserve_n=n), pkg.Context(0, stream=sb, reserve_n=n)
+    dx = torch.from_numpy(x).cuda()
+    cap = pkg.max_compressed_bytes(n)
+    sent = torch.empty(cap, dtype=torch.uint8, device="cuda"); recv = torch.empty(cap, dtype=torch.uint8, device="cuda")
+    y = torch.empty(n, dtype=torch.float32, device="cuda")
+    prog = torch.zeros(k, 2, dtype=torch.int64, device="cuda")
+    res = torch.zeros(2 * k, 2, dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
+
+    def piped():
+        # producer first, then consumer: each side's work sits in its HIP stream before the device gets to it, as
+        # with a transport thread of its own (launching piece by piece from one host thread starves the device)
+        evs = []
+        with torch.cuda.stream(sa):
+            ca.compress_begin(n, eb, sent)
+            for i in range(k):
+                ca.compress_chunks_async(dx, bounds[i], bounds[i + 1], prog[i], res[i])
+                ev = torch.cuda.Event(); ev.record(sa); evs.append(ev)
+        with torch.cuda.stream(sb):
+            for i in range(k):
+                sb.wait_event(evs[i])
+                pkg.forward_async(recv, sent, n, prog[i - 1] if i else None, prog[i], hip_stream=sb.cuda_stream)
+                cb.decompress_chunks_async(recv, cap, n, bounds[i], bounds[i + 1], y[bounds[i] * 5120:], res[k + i])
+
+    def serial():
+        with torch.cuda.stream(sa):
+            ca.compress_async(dx, eb, sent, res[0])
+            pkg.forward_async(recv, sent, n, None, prog[k - 1], hip_stream=sa.cuda_stream)
+            ca.decompress_async(recv, n, y, res[1], in_bytes=cap)
+
+    def wall(fn, reps):
+        fn(); torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    ms_p = wall(piped, 10)
+    assert (res.cpu().numpy()[:, 1] == 0).all()
+    err = (y.double() - dx.double()).abs().max().item()
+    assert err <= eb * (1 + 1e-9), (err, eb)
+    ms_s = wall(serial, 10)
+    ca.close(); cb.close()
+    return {"pieces": k, "chunks_per_piece": per, "ms_pipelined_two_streams": round(ms_p, 4), "ms_serial_one_stream": round(ms_s, 4),
+            "note": "compress -> forward (device copy) -> decompress of the headline field; wall clock per pass"}
+
+
 def bench_sweep(pkg, torch, workloads):
     """Workload 4: noise fraction {0, .25, .5, 1} x relative bound {1e-2 .. 1e-6} on 2^27 values."""
     import numpy as np
@@ -358,7 +417,8 @@ def main():
     ap.add_argument("--rel-eb", type=float, default=1e-3)
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="elements the oracle is timed on (0 = skip)")
     ap.add_argument("--table", default=None, help="also run all workloads and bounds and write a markdown table to this path")
-    ap.add_argument("--no-extras", action="store_true", help="only the headline workload (no ring8 / bcast64 / sweep keys)")
+    ap.add_argument("--no-extras", action="store_true", help="only the headline workload (no pipe / ring8 / bcast64 / sweep keys)")
+    ap.add_argument("--extras", default="pipe,ring8,bcast64,sweep", help="which of the other workloads to run (comma separated)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -469,8 +529,12 @@ def main():
     ctx.close()
     del dx, dlocal, stream, stream2, y
     torch.cuda.empty_cache()
-    if not args.no_extras:
-        for key, fn in (("ring8", bench_ring8), ("bcast64", bench_bcast64), ("sweep", bench_sweep)):
+    extras = [] if args.no_extras else [e for e in args.extras.split(",") if e]
+    if "pipe" in extras:
+        line["pipe"] = bench_pipe(pkg, torch, workloads, x, eb)
+        torch.cuda.empty_cache()
+    for key, fn in (("ring8", bench_ring8), ("bcast64", bench_bcast64), ("sweep", bench_sweep)):
+        if key in extras:
             line[key] = fn(pkg, torch, workloads)
             torch.cuda.empty_cache()
     if args.table:

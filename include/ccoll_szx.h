@@ -170,6 +170,36 @@ int ccoll_reduce_step_op_async(ccoll_ctx *ctx, int op, const float *d_local, siz
 int ccoll_szx_decompress_static(int device, void *hip_stream, const void *d_in, size_t in_bytes,
                                 float *d_out, size_t n, unsigned long long *d_result);
 
+/* PIPE-SZx (Sec. III-E.2): the paper compresses a message in chunks so that the transfer of what is coded
+ * can go on while the rest is still being coded, and decompresses what has arrived while the rest is still on
+ * its way.  Here one stream (one header, one front index: the same bytes as ccoll_szx_compress gives) is
+ * written by several launches, each coding a piece of consecutive chunks:
+ *   ccoll_szx_compress_begin       starts a stream of n elements in d_out (writes the header with a total of 0);
+ *   ccoll_szx_compress_chunks_async  codes chunks [chunk_first, chunk_end) of d_in (the address of element 0 of the
+ *     whole input).  Pieces follow each other without gaps from chunk 0 on; every piece but the last ends at a
+ *     multiple of CCOLL_PIECE_CHUNKS chunks.  When the launch has completed, the front index entries and payloads
+ *     of all chunks below chunk_end are final, and d_progress (device, 8-byte aligned, two 64-bit words, may be
+ *     NULL) holds {chunk_end, stream bytes that are final}; the last piece also writes the header's total.
+ *     d_result as for the other *_async calls ({stream bytes so far, status}).
+ *   No other compress or reduce call may use the context between begin and the last piece (the pieces share the
+ *   context's scan state); such a call ends the open stream, and further pieces return CCOLL_EINVAL.
+ *   ccoll_szx_decompress_chunks_async  decodes chunks [chunk_first, chunk_end) of a stream of n elements of which
+ *     only the header, the front index entries and the payloads of the chunks below chunk_end need to have arrived
+ *     (in_bytes: the bytes that are there; the header's total is not looked at).  d_out[0] receives element
+ *     5120 * chunk_first.
+ *   ccoll_szx_forward_async  stands in for the transport on one device: copies what has become final between two
+ *     progress words (d_from = NULL: the start of the stream) from d_src to the same offsets of d_dst, on any
+ *     stream of `device`; with the last piece the final header goes along.  Enqueue it behind the piece (an event). */
+#define CCOLL_PIECE_CHUNKS 12
+int ccoll_szx_compress_begin(ccoll_ctx *ctx, size_t n, float abs_eb, void *d_out, size_t out_cap);
+int ccoll_szx_compress_chunks_async(ccoll_ctx *ctx, const float *d_in, size_t chunk_first, size_t chunk_end,
+                                    unsigned long long *d_progress, unsigned long long *d_result);
+int ccoll_szx_decompress_chunks_async(ccoll_ctx *ctx, const void *d_in, size_t in_bytes, size_t n,
+                                      size_t chunk_first, size_t chunk_end, float *d_out,
+                                      unsigned long long *d_result);
+int ccoll_szx_forward_async(int device, void *hip_stream, void *d_dst, const void *d_src, size_t n,
+                            const unsigned long long *d_from, const unsigned long long *d_upto);
+
 /* Waits for the context's stream.  Returns the status of the *_async calls that kept their result in the
  * context (d_result = NULL) and were enqueued since the previous ccoll_wait: CCOLL_OK if all of them went
  * well, else the code of the latest one that failed.  *bytes (may be NULL) receives the byte count of the

@@ -8,5 +8,5 @@ built library, or without a GPU, the calls raise.
 from .binding import (  # noqa: F401
     BLOCK, CHUNK, OK, EINVAL, ENOSPC, ECORRUPT, EHIP, ETIMEDOUT, OP_SUM, OP_MAX, OP_MIN,
     CcollError, Context, load_library, library_path, max_compressed_bytes, exported_symbols,
-    decompress_static, STATIC_MAX_ELEMS,
+    decompress_static, STATIC_MAX_ELEMS, forward_async,
 )

@@ -36,6 +36,15 @@ _SIGNATURES = {
                                                          ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t),
                                                          ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_void_p),
                                                          ctypes.c_void_p]),
+    "ccoll_szx_compress_begin": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float, ctypes.c_void_p,
+                                                ctypes.c_size_t]),
+    "ccoll_szx_compress_chunks_async": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t,
+                                                       ctypes.c_void_p, ctypes.c_void_p]),
+    "ccoll_szx_decompress_chunks_async": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t,
+                                                         ctypes.c_size_t, ctypes.c_size_t, ctypes.c_void_p,
+                                                         ctypes.c_void_p]),
+    "ccoll_szx_forward_async": (ctypes.c_int, [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]),
     "ccoll_szx_index": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t]),
     "ccoll_szx_index_async": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_size_t,
                                              ctypes.c_void_p]),
@@ -112,6 +121,15 @@ def decompress_static(stream, n: int, out, result, in_bytes: int | None = None, 
     return load_library().ccoll_szx_decompress_static(device, ctypes.c_void_p(hip_stream), _ptr(stream),
                                                       stream.numel() if in_bytes is None else in_bytes, _ptr(out), n,
                                                       _ptr(result))
+
+
+def forward_async(dst, src, n: int, frm, upto, device: int = 0, hip_stream=None) -> int:
+    """ccoll_szx_forward_async: copies what became final between two progress words (the transport's stand-in)."""
+    import torch
+    if hip_stream is None:
+        hip_stream = torch.cuda.current_stream(device).cuda_stream
+    return load_library().ccoll_szx_forward_async(device, ctypes.c_void_p(hip_stream), _ptr(dst), _ptr(src), n,
+                                                  _ptr(frm), _ptr(upto))
 
 
 class CcollError(RuntimeError):
@@ -224,6 +242,21 @@ class Context:
         return self._lib.ccoll_szx_decompress_ranges_async(self._h, _ptr(stream),
                                                            stream.numel() if in_bytes is None else in_bytes, n,
                                                            len(firsts), f, c, o, _ptr(result))
+
+    # ---- one stream written and read piece by piece (Sec. III-E.2) ----
+    def compress_begin(self, n: int, abs_eb: float, out):
+        rc = self._lib.ccoll_szx_compress_begin(self._h, n, abs_eb, _ptr(out), out.numel())
+        if rc:
+            raise CcollError(rc, "ccoll_szx_compress_begin")
+
+    def compress_chunks_async(self, x, chunk_first: int, chunk_end: int, progress=None, result=None) -> int:
+        return self._lib.ccoll_szx_compress_chunks_async(self._h, _ptr(x), chunk_first, chunk_end, _ptr(progress),
+                                                         _ptr(result))
+
+    def decompress_chunks_async(self, stream, in_bytes: int, n: int, chunk_first: int, chunk_end: int, out,
+                                result=None) -> int:
+        return self._lib.ccoll_szx_decompress_chunks_async(self._h, _ptr(stream), in_bytes, n, chunk_first,
+                                                           chunk_end, _ptr(out), _ptr(result))
 
     def index(self, stream, n: int):
         """ccoll_szx_index: checks header and front index once; decompress_range_indexed then skips that."""

@@ -93,6 +93,11 @@ struct Params {
   u32 no_total;               // k_publish: the call reports no byte count
   u32 ticket_sel;             // which of the two ticket counters this launch draws from
   u32 spin_limit;             // polls after which a scan wait gives up
+  u32 scan_epoch;             // tag of the look-back status words: the call's epoch, or, for the pieces of a stream that
+                              // is compressed piece by piece, the epoch of the call that began the stream
+  u32 scan_chunks;            // incoming stream: index entries to walk (all, or those that have arrived of an open stream)
+  u32 open_stream;            // incoming stream: still being written (the header's total is not final)
+  unsigned long long* progress;  // compress: {chunks coded, stream bytes final} of the launch, or null
   u32 idx_epoch;              // decompress with kept chunk offsets: the epoch of the ccoll_szx_index call that made them
   u32 index_call;             // k_index_scan runs for ccoll_szx_index: a malformed stream is also noted in ws->idx_bad
   unsigned char* spill;       // per-wavefront slots for payloads whose place in the stream is not known yet
@@ -197,7 +202,7 @@ __device__ __forceinline__ void publish_size(u64* stat, u32 c, u64 mine, u32 epo
 // (error raised).  Four windows of 64 status words are fetched per round trip.
 __device__ __forceinline__ bool lookback(u64* stat, u32 c, u64 mine, const Params& P, u64& excl_out) {
   const u32 lane = threadIdx.x & 63u;
-  const u64 tag = (u64)P.epoch << kEpochShift;
+  const u64 tag = (u64)P.scan_epoch << kEpochShift;
   u64 excl = 0;
   if (c > 0) {
     long long look = (long long)c - 1;
@@ -595,7 +600,7 @@ __device__ __forceinline__ bool header_ok(const unsigned char* s, const Params& 
   if (h[5] != P.nchunks) return false;
   const u64 total = (u64)h[6] | ((u64)h[7] << 32);
   const u64 front = kHeader + 4ull * P.nchunks;
-  if (total < front || total > P.in_bytes) return false;
+  if (!P.open_stream && (total < front || total > P.in_bytes)) return false;
   return true;
 }
 
@@ -613,6 +618,42 @@ __global__ void k_empty_stream(Params P) {
     st_dev(&P.ws->total, (u64)kHeader);
     if (!ok) raise_error(P, CCOLL_ECORRUPT, 1);
   }
+}
+
+// A stream that is compressed piece by piece (Sec. III-E.2): the header goes first, with a total of 0 that the last
+// piece replaces, so that a receiver can check what has arrived of the stream before all of it exists.
+__global__ void k_begin_stream(Params P) {
+  if (threadIdx.x == 0) {
+    u32* h = (u32*)P.out;
+    h[0] = 0x31585343u; h[1] = (u32)kBlock | ((u32)kChunk << 16);
+    h[2] = (u32)P.n; h[3] = (u32)(P.n >> 32); h[4] = P.eb_bits; h[5] = P.nchunks; h[6] = 0; h[7] = 0;
+    st_dev(&P.ws->total, (u64)kHeader);
+  }
+}
+
+// What a transport would send of a stream that is still being written: the front index entries of chunks
+// [from.chunks, upto.chunks), the payload bytes [from.bytes, upto.bytes) and, once the last chunk is among them,
+// the header; copied to the same offsets of dst.  from / upto: {chunks coded, stream bytes final} as a compress
+// call leaves them; from == null: the start of the stream.
+__global__ void __launch_bounds__(256) k_forward(unsigned char* dst, const unsigned char* src, u32 nchunks,
+                                                 const unsigned long long* from, const unsigned long long* upto) {
+  const u64 front = kHeader + 4ull * nchunks;
+  const u64 c_lo = from ? from[0] : 0ull, b_lo = from ? from[1] : front;
+  const u64 c_hi = upto[0], b_hi = upto[1];
+  const u64 tid = (u64)blockIdx.x * blockDim.x + threadIdx.x, nth = (u64)gridDim.x * blockDim.x;
+  if (c_hi < c_lo || b_hi < b_lo || b_lo < front || c_hi > nchunks) return;      // not a pair of progress words of one stream
+  const u32* s32 = (const u32*)src; u32* d32 = (u32*)dst;
+  for (u64 i = kHeader / 4 + c_lo + tid; i < kHeader / 4 + c_hi; i += nth) d32[i] = s32[i];
+  // payload: whole 16-byte vectors where source and destination (same offset in both) are aligned, words at the ends
+  const u64 w_lo = b_lo / 4, w_hi = b_hi / 4;
+  const bool al = ((((uintptr_t)src) | ((uintptr_t)dst)) & 15u) == 0;
+  u64 v_lo = (w_lo + 3) & ~3ull, v_hi = w_hi & ~3ull;
+  if (!al || v_lo > v_hi) { v_lo = w_hi; v_hi = w_hi; }
+  for (u64 i = w_lo + tid; i < (v_lo < w_hi ? v_lo : w_hi); i += nth) d32[i] = s32[i];
+  for (u64 i = v_lo / 4 + tid; i < v_hi / 4; i += nth) ((uint4*)dst)[i] = ((const uint4*)src)[i];
+  for (u64 i = v_hi + tid; i < w_hi; i += nth) d32[i] = s32[i];
+  if (c_hi == nchunks && tid < kHeader / 4) d32[tid] = s32[tid];
+  else if (c_lo == 0 && tid < kHeader / 4) d32[tid] = s32[tid];                    // the open header travels with the first piece
 }
 
 // n == 0: the stream must be a bare header.
@@ -637,8 +678,8 @@ __global__ void __launch_bounds__(1024) k_index_scan(Params P) {
   const unsigned char* s = (const unsigned char*)(P.cin ? P.cin : P.in);
   const u32* ci = (const u32*)(s + kHeader);
   const u32 tid = threadIdx.x, lane = tid & 63u, wv = tid >> 6;
-  const u32 n = P.nchunks;
-  const u32 nlast = (u32)((P.n - (u64)(n ? n - 1 : 0) * kChunk + kBlock - 1) / kBlock);   // blocks of the last chunk
+  const u32 n = P.scan_chunks, nall = P.nchunks;       // entries walked (those that have arrived), entries of the stream
+  const u32 nlast = (u32)((P.n - (u64)(nall ? nall - 1 : 0) * kChunk + kBlock - 1) / kBlock);   // blocks of the last chunk
   const bool al16 = (((uintptr_t)ci) & 15u) == 0;
   const u32 tile = blockIdx.x * kScanTile;
   u32 why = 0;
@@ -683,7 +724,7 @@ __global__ void __launch_bounds__(1024) k_index_scan(Params P) {
   for (int i = 0; i < 8; ++i) {
     const u32 c = a + i;
     if (c < n) {
-      const u32 nbc = (c + 1 == n) ? nlast : (u32)kBpc;
+      const u32 nbc = (c + 1 == nall) ? nlast : (u32)kBpc;
       if ((v[i] & 3u) || v[i] < 8u + 4u * nbc || v[i] > kMaxPayload) { why = 2; v[i] = 0; }
     }
     rel[tid * 9 + i] = local;                         // prefix inside the thread; valid sizes are < 2^15
@@ -710,9 +751,10 @@ __global__ void __launch_bounds__(1024) k_index_scan(Params P) {
     if (tile + e < n) P.offs[tile + e] = carry + rel[(e >> 3) * 9 + (e & 7u)];
   }
   if (tid == 1023 && tile + kScanTile >= n) {         // the workgroup of the last tile: the sizes must add up to the header's total
-    const u64 front = kHeader + 4ull * n;
+    const u64 front = kHeader + 4ull * nall;
     const u64 total = (u64)((const u32*)s)[6] | ((u64)((const u32*)s)[7] << 32);
-    if (!why && front + carry + excl + local != total) why = 5;
+    const u64 sum = front + carry + excl + local;
+    if (!why && (P.open_stream ? sum > P.in_bytes : sum != total)) why = 5;
   }
   if (tid == 0 && blockIdx.x == 0 && !header_ok(s, P)) why = 1;
   if (why) raise_error(P, CCOLL_ECORRUPT, why);
@@ -1387,6 +1429,8 @@ __device__ __forceinline__ void place_staged(u32 c, const ChunkOut& o, u64 off, 
   if (lane == 0) {
     if (!fits) raise_error(P, CCOLL_ENOSPC);
     if (c + 1 == P.nchunks) write_header(P, front + off + o.payload);
+    else if (c + 1 == P.c1) st_dev(&P.ws->total, front + off + o.payload);      // a piece of a stream: bytes so far
+    if (c + 1 == P.c1 && P.progress) { P.progress[0] = P.c1; P.progress[1] = front + off + o.payload; }
   }
   if (!fits) return;
   unsigned char* dst = (unsigned char*)P.out + front + off;
@@ -1415,7 +1459,8 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
   const u32 lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
   unsigned char* gout = (unsigned char*)P.out;
   const u32 nfull = (u32)(P.n / kChunk);
-  const u32 ngroups = (P.nchunks + NW - 1) / NW;
+  const u32 g0 = P.c0 / NW;                                   // the launch codes chunks [c0, c1): groups [g0, ngroups)
+  const u32 ngroups = (P.c1 + NW - 1) / NW;
   const GrpMasks gm = grp_masks();
   // two spill slots per wavefront, used in turns: one may still hold the parked payload of the previous turn
   // while the chunk being coded outgrows the LDS stage into the other
@@ -1428,7 +1473,7 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
   u64* ticket = &P.ws->ticket[P.ticket_sel];
   if (threadIdx.x == 0) {
     if (blockIdx.x == 0) st_dev(&P.ws->ticket[P.ticket_sel ^ 1u], 0ull);      // for the next launch on the stream
-    const u64 t = __hip_atomic_fetch_add(ticket, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const u64 t = (u64)g0 + __hip_atomic_fetch_add(ticket, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     g.next[1] = t < (u64)ngroups ? (u32)t : ngroups;
   }
   __syncthreads();
@@ -1445,9 +1490,9 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
     EncWaveLds<CAP>& Lp = Ls[par ^ 1u];                       // where the previous turn's payload is
     // the next group is asked for now, it is needed after the barrier
     u64 tnext = 0;
-    if (threadIdx.x == 0) tnext = __hip_atomic_fetch_add(ticket, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) tnext = (u64)g0 + __hip_atomic_fetch_add(ticket, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const u32 c = q * NW + wv;
-    const bool have = c < P.nchunks;
+    const bool have = c < P.c1;
     ChunkOut o; o.payload = 0; o.meta_len = 0; o.bodies = 0; o.flushed = 0;
     if (have) o = c < nfull ? encode_chunk<true, CAP>(src, c, P, gm, L, slot) : encode_chunk<false, CAP>(src, c, P, gm, L, slot);
     // The first wavefront walks the scan for the previous group's place while the slower wavefronts of the
@@ -1470,7 +1515,7 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
       u32 gtot = 0;
 #pragma unroll
       for (int j = 0; j < NW; ++j) gtot += g.size[ts][j];
-      publish_size(P.stat, q, gtot, P.epoch);
+      publish_size(P.stat, q, gtot, P.scan_epoch);
     }
     if (pend) {
       if (g.pres[par] == 0) { dead = true; break; }           // the scan wait was abandoned: error raised, everyone leaves
@@ -1507,6 +1552,7 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
 constexpr int kEncWaves = 12;
 constexpr u32 kEncCap = 6240;                        // body bytes a wavefront stages at a time; what outgrows them goes to the spill slot
 constexpr u32 kSpillSlot = 22272;                    // >= kMetaMax + 40 * 544 + 16, a multiple of 256: a whole payload
+static_assert(CCOLL_PIECE_CHUNKS == kEncWaves, "a piece of a stream ends where a group of chunks ends");
 struct __align__(16) CompressSmem { EncWaveLds<kEncCap> wave[kEncWaves][2]; GroupLds<kEncWaves> g; };
 
 __global__ void __launch_bounds__(64 * kEncWaves) __attribute__((amdgpu_waves_per_eu(3, 3))) k_compress(Params P) {
@@ -1591,6 +1637,8 @@ struct ccoll_ctx {
   u64 own_slot;           // bit i: the call of epoch (epoch - i) keeps its result in the context (not in a caller's slot)
   u32 idx_epoch;          // epoch of the ccoll_szx_index call whose offsets are kept
   size_t spill_waves;     // wavefronts the spill area has slots for
+  bool pipe_open;         // a stream is being compressed piece by piece (ccoll_szx_compress_begin)
+  size_t pipe_n, pipe_cap, pipe_next; void* pipe_out; float pipe_eb; u32 pipe_epoch;
   bool last_total;        // that call reports a byte count
   int grid_compress, grid_decompress, grid_reduce;   // workgroups that are resident at once
   u32 ticket_sel;         // ticket counter of the next ticketed launch (0 / 1); the other one is being zeroed by the last
@@ -1615,7 +1663,7 @@ bool hip_ok(hipError_t e, const char* what) {
 int reset_workspace(ccoll_ctx* c) {
   if (!HIP_OK(hipMemsetAsync(c->ws, 0, sizeof(Workspace), c->stream))) return CCOLL_EHIP;
   if (c->stat && !HIP_OK(hipMemsetAsync(c->stat, 0, c->cap_chunks * sizeof(u64), c->stream))) return CCOLL_EHIP;
-  c->epoch = 0; c->waited_epoch = 0; c->last_epoch = 0; c->own_slot = 0; c->idx_ptr = nullptr;
+  c->epoch = 0; c->waited_epoch = 0; c->last_epoch = 0; c->own_slot = 0; c->idx_ptr = nullptr; c->pipe_open = false;
   c->ticket_sel = 0;
   return CCOLL_OK;
 }
@@ -1633,6 +1681,7 @@ int prepare(ccoll_ctx* c, size_t n, Params& P) {
   memset(&P, 0, sizeof(P));
   P.n = n; P.nchunks = (u32)nchunks; P.c0 = 0; P.c1 = (u32)nchunks;
   P.epoch = ++c->epoch;
+  P.scan_epoch = P.epoch; P.scan_chunks = P.nchunks;
   c->own_slot <<= 1;
   P.ws = c->ws; P.stat = c->stat; P.offs = c->offs;
   P.spin_limit = c->spin_limit;
@@ -1682,7 +1731,7 @@ int ccoll_create(ccoll_ctx** out, int device, void* hip_stream) {
   ccoll_ctx* c = new (std::nothrow) ccoll_ctx();
   if (!c) return CCOLL_EHIP;
   c->device = device; c->stream = (hipStream_t)hip_stream; c->stat = nullptr; c->cap_chunks = 0;
-  c->ws = nullptr; c->spill = nullptr; c->spin_limit = kSpinLimit; c->idx_ptr = nullptr; c->idx_bytes = 0; c->idx_n = 0; c->host_ws = nullptr; c->offs = nullptr; c->last_epoch = 0; c->last_total = false; c->waited_epoch = 0; c->own_slot = 0; c->idx_epoch = 0; c->spill_waves = 0;
+  c->ws = nullptr; c->spill = nullptr; c->spin_limit = kSpinLimit; c->idx_ptr = nullptr; c->idx_bytes = 0; c->idx_n = 0; c->host_ws = nullptr; c->offs = nullptr; c->last_epoch = 0; c->last_total = false; c->waited_epoch = 0; c->own_slot = 0; c->idx_epoch = 0; c->spill_waves = 0; c->pipe_open = false;
   if (!HIP_OK(hipMalloc((void**)&c->ws, sizeof(Workspace))) ||
       !HIP_OK(hipHostMalloc((void**)&c->host_ws, sizeof(Workspace), hipHostMallocDefault))) {
     ccoll_destroy(c); return CCOLL_EHIP;
@@ -1759,6 +1808,7 @@ int ccoll_szx_compress_async(ccoll_ctx* c, const float* d_in, size_t n, float ab
   int rc = prepare(c, n, P);
   if (rc) return rc;
   if (out_cap < kHeader + 4ull * P.nchunks) return CCOLL_ENOSPC;
+  c->pipe_open = false;                        // the scan words are about to belong to this stream
   P.in = d_in; P.out = d_out; P.out_cap = out_cap;
   P.eb = abs_eb; P.e_eb = ilogbf(abs_eb); memcpy(&P.eb_bits, &abs_eb, 4);
   P.aligned16 = (((uintptr_t)d_in & 15) == 0);
@@ -1837,6 +1887,88 @@ int ccoll_szx_decompress_range_indexed_async(ccoll_ctx* c, const void* d_in, siz
   return after_launch(c, P, d_result, false);
 }
 
+int ccoll_szx_compress_begin(ccoll_ctx* c, size_t n, float abs_eb, void* d_out, size_t out_cap) {
+  if (!c || !d_out || !eb_valid(abs_eb) || n == 0 || n > ((size_t)1 << 31) || ((uintptr_t)d_out & 3)) return CCOLL_EINVAL;
+  DeviceGuard g(c->device);
+  if (!g.ok) return CCOLL_EHIP;
+  Params P;
+  int rc = prepare(c, n, P);
+  if (rc) return rc;
+  if (out_cap < kHeader + 4ull * P.nchunks) return CCOLL_ENOSPC;
+  P.out = d_out; P.out_cap = out_cap; memcpy(&P.eb_bits, &abs_eb, 4);
+  hipLaunchKernelGGL(k_begin_stream, dim3(1), dim3(64), 0, c->stream, P);
+  rc = after_launch(c, P, nullptr, true);
+  if (rc) return rc;
+  c->pipe_open = true; c->pipe_n = n; c->pipe_cap = out_cap; c->pipe_next = 0; c->pipe_out = d_out; c->pipe_eb = abs_eb;
+  c->pipe_epoch = P.epoch;
+  return CCOLL_OK;
+}
+
+int ccoll_szx_compress_chunks_async(ccoll_ctx* c, const float* d_in, size_t chunk_first, size_t chunk_end,
+                                    unsigned long long* d_progress, unsigned long long* d_result) {
+  if (!c || !d_in || !c->pipe_open || ((uintptr_t)d_in & 3) || ((uintptr_t)d_progress & 7)) return CCOLL_EINVAL;
+  const size_t nchunks = (c->pipe_n + kChunk - 1) / kChunk;
+  if (chunk_first != c->pipe_next || chunk_end <= chunk_first || chunk_end > nchunks) return CCOLL_EINVAL;
+  if (chunk_end != nchunks && chunk_end % CCOLL_PIECE_CHUNKS) return CCOLL_EINVAL;
+  DeviceGuard g(c->device);
+  if (!g.ok) return CCOLL_EHIP;
+  Params P;
+  int rc = prepare(c, c->pipe_n, P);
+  if (rc) return rc;
+  P.in = d_in; P.out = c->pipe_out; P.out_cap = c->pipe_cap;
+  const float eb = c->pipe_eb;
+  P.eb = eb; P.e_eb = ilogbf(eb); memcpy(&P.eb_bits, &eb, 4);
+  P.aligned16 = (((uintptr_t)d_in & 15) == 0);
+  P.c0 = (u32)chunk_first; P.c1 = (u32)chunk_end;
+  P.scan_epoch = c->pipe_epoch;                // the scan goes on where the piece before stopped
+  P.progress = d_progress;
+  const u32 ngroups = (u32)((chunk_end + kEncWaves - 1) / kEncWaves - chunk_first / kEncWaves);
+  const u32 grid = grid_for(c->grid_compress, ngroups);
+  P.ticket_sel = c->ticket_sel; c->ticket_sel ^= 1u; P.spill = c->spill;
+  hipLaunchKernelGGL(k_compress, dim3(grid), dim3(64 * kEncWaves), 0, c->stream, P);
+  rc = after_launch(c, P, d_result, true);
+  if (rc) { c->pipe_open = false; return rc; }
+  c->pipe_next = chunk_end;
+  if (chunk_end == nchunks) c->pipe_open = false;
+  return CCOLL_OK;
+}
+
+int ccoll_szx_decompress_chunks_async(ccoll_ctx* c, const void* d_in, size_t in_bytes, size_t n, size_t chunk_first,
+                                      size_t chunk_end, float* d_out, unsigned long long* d_result) {
+  if (!c || !d_in || !d_out || n == 0 || n > ((size_t)1 << 31)) return CCOLL_EINVAL;
+  if (((uintptr_t)d_in & 3) || ((uintptr_t)d_out & 3)) return CCOLL_EINVAL;
+  const size_t nchunks = (n + kChunk - 1) / kChunk;
+  if (chunk_first >= chunk_end || chunk_end > nchunks) return CCOLL_EINVAL;
+  DeviceGuard g(c->device);
+  if (!g.ok) return CCOLL_EHIP;
+  Params P;
+  int rc = prepare(c, n, P);
+  if (rc) return rc;
+  if (in_bytes < kHeader + 4ull * P.nchunks) return CCOLL_ECORRUPT;
+  P.in = d_in; P.in_bytes = in_bytes; P.out = d_out;
+  P.first = chunk_first * (size_t)kChunk;
+  P.count = (chunk_end * (size_t)kChunk < n ? chunk_end * (size_t)kChunk : n) - P.first;
+  P.aligned16 = (((uintptr_t)d_out & 15) == 0);
+  P.c0 = (u32)chunk_first; P.c1 = (u32)chunk_end;
+  P.scan_chunks = (u32)chunk_end; P.open_stream = 1;       // only what has arrived is checked; the total may not be final
+  c->idx_ptr = nullptr;
+  hipLaunchKernelGGL(k_index_scan, dim3((P.scan_chunks + kScanTile - 1) / kScanTile), dim3(1024), 0, c->stream, P);
+  hipLaunchKernelGGL(k_decompress, dim3((P.c1 - P.c0 + kDecWaves - 1) / kDecWaves), dim3(64 * kDecWaves), 0, c->stream, P);
+  return after_launch(c, P, d_result, false);
+}
+
+int ccoll_szx_forward_async(int device, void* hip_stream, void* d_dst, const void* d_src, size_t n,
+                            const unsigned long long* d_from, const unsigned long long* d_upto) {
+  if (!d_dst || !d_src || !d_upto || n == 0 || n > ((size_t)1 << 31)) return CCOLL_EINVAL;
+  if (((uintptr_t)d_dst & 3) || ((uintptr_t)d_src & 3) || ((uintptr_t)d_from & 7) || ((uintptr_t)d_upto & 7)) return CCOLL_EINVAL;
+  DeviceGuard g(device);
+  if (!g.ok) return CCOLL_EHIP;
+  const u32 nchunks = (u32)((n + kChunk - 1) / kChunk);
+  hipLaunchKernelGGL(k_forward, dim3(512), dim3(256), 0, (hipStream_t)hip_stream, (unsigned char*)d_dst,
+                     (const unsigned char*)d_src, nchunks, d_from, d_upto);
+  return HIP_OK(hipGetLastError()) ? CCOLL_OK : CCOLL_EHIP;
+}
+
 int ccoll_szx_decompress_ranges_async(ccoll_ctx* c, const void* d_in, size_t in_bytes, size_t n, size_t nranges,
                                       const size_t* first, const size_t* count, float* const* d_out,
                                       unsigned long long* d_result) {
@@ -1894,6 +2026,7 @@ int ccoll_reduce_step_op_async(ccoll_ctx* c, int op, const float* d_local, size_
   if (rc) return rc;
   if (cin_bytes < kHeader + 4ull * P.nchunks) return CCOLL_ECORRUPT;
   if (cout_cap < kHeader + 4ull * P.nchunks) return CCOLL_ENOSPC;
+  c->pipe_open = false;
   P.local = d_local; P.cin = d_cin; P.in_bytes = cin_bytes; P.out = d_cout; P.out_cap = cout_cap;
   P.eb = abs_eb; P.e_eb = ilogbf(abs_eb); memcpy(&P.eb_bits, &abs_eb, 4);
   P.aligned16 = (((uintptr_t)d_local & 15) == 0);
@@ -1947,7 +2080,7 @@ int ccoll_szx_decompress_static(int device, void* hip_stream, const void* d_in, 
   Params P;
   memset(&P, 0, sizeof(P));
   P.n = n; P.nchunks = (u32)((n + kChunk - 1) / kChunk); P.c0 = 0; P.c1 = P.nchunks;
-  P.epoch = 1;                                                  // the words are cleared per call, not tagged
+  P.epoch = 1; P.scan_epoch = 1; P.scan_chunks = P.nchunks;     // the words are cleared per call, not tagged
   P.ws = &sc->ws; P.offs = sc->offs; P.spin_limit = kSpinLimit;
   P.in = d_in; P.in_bytes = in_bytes; P.out = d_out; P.first = 0; P.count = n;
   P.aligned16 = (((uintptr_t)d_out & 15) == 0);
