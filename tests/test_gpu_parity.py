@@ -427,6 +427,37 @@ def test_reduce_step_max_min_match_oracle(ctx, op):
         assert np.array_equal(got.cpu().numpy(), want), (op, e)
 
 
+def test_error_propagation_on_the_device(ctx):
+    """The chains of tests/test_error_propagation.py (Sec. III-B: Theorem 1, Corollaries 1 and 2, Theorem 2) through
+    the GPU path: every stream equals the oracle's, so the statistics are the oracle's; the deterministic bounds
+    (P eb for Sum, Max, Min; eb for the Average) and the sqrt(P) growth of the Sum's error are checked on what
+    the device decoded."""
+    import sys, os
+    import paper_2304_03890_amd as pkg
+    sys.path.insert(0, os.path.dirname(__file__))
+    from test_error_propagation import rank_fields, chain_stats, check_bounds
+    P, n = 8, 5120 * 40 + 333
+    eb = float(np.float32(2e-3))
+    parts = rank_fields(P, n)
+    code = {"sum": pkg.OP_SUM, "max": pkg.OP_MAX, "min": pkg.OP_MIN}
+    for op in ("sum", "max", "min"):
+        errs, exact = chain_stats(parts, eb, op,
+                                  lambda x, e: ctx.compress(dev(x), e).clone(),
+                                  lambda loc, s, e, o: ctx.reduce_step(dev(loc), s, e, op=code[o]).clone(),
+                                  lambda s, m: ctx.decompress(s, m).cpu().numpy())
+        check_bounds(parts, eb, errs, exact, op)
+        want, _ = chain_stats(parts, np.float32(eb), op, ref.compress,
+                              lambda loc, s, e, o: ref.reduce_step(loc, s, e, op=o), ref.decompress)
+        for a, b in zip(errs, want):
+            assert np.array_equal(a, b), op
+        if op == "sum":
+            sigma1 = errs[0].std()
+            for k in range(2, P + 1):
+                assert 0.6 < errs[k - 1].std() / (np.sqrt(k) * sigma1) < 1.4
+                assert (np.abs(errs[k - 1]) <= (2.0 / 3.0) * np.sqrt(k) * eb).mean() >= 0.9544
+                assert (np.abs(errs[k - 1] / k) <= eb * (1 + 1e-6) + 1e-6).all()
+
+
 def test_reduce_step_rejects_unknown_op(ctx):
     import paper_2304_03890_amd as pkg
     x = workloads.vector_1d(5120)
