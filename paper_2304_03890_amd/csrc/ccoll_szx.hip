@@ -104,6 +104,27 @@ struct Params {
 };
 
 
+// Parameters that the kernels need once per turn or less (the scan words, the output, capacities, epochs) are read
+// from the kernel argument segment where they are used, by a scalar load the compiler may not hoist or keep: held
+// in registers for the whole kernel they would push the coder's hot loop, which is short of scalar registers, into
+// spilling them through vector registers and scratch memory.  Every kernel that uses these helpers takes the
+// Params block as its first argument.
+template <u32 OFF>
+__device__ __forceinline__ u32 karg32() {
+  u32 v;
+  asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(__builtin_amdgcn_kernarg_segment_ptr()), "n"(OFF));
+  return v;
+}
+template <u32 OFF>
+__device__ __forceinline__ u64 karg64() {
+  u64 v;
+  asm volatile("s_load_dwordx2 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(__builtin_amdgcn_kernarg_segment_ptr()), "n"(OFF));
+  return v;
+}
+#define KARG32(field) karg32<(u32)offsetof(Params, field)>()
+#define KARG64(field) karg64<(u32)offsetof(Params, field)>()
+#define KARGP(type, field) ((type)karg64<(u32)offsetof(Params, field)>())
+
 // ---------------------------------------------------------------------------------------------
 // small device helpers
 // ---------------------------------------------------------------------------------------------
@@ -188,9 +209,12 @@ __device__ __forceinline__ void st_dev(u64* p, u64 v) { __hip_atomic_store(p, v,
 // metadata, 7 block body, 8 scan wait); reported on stderr by ccoll_wait when CCOLL_DEBUG is set.
 __device__ __forceinline__ void raise_error(const Params& P, int code, u32 detail = 0) {
   // codes are negative; keep the most severe (most negative) one of this epoch
-  u64 word = ((u64)P.epoch << 8) | ((u64)(u32)(-code) << 4) | (u64)(detail & 15u);
-  __hip_atomic_fetch_max(&P.ws->err, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (P.index_call) __hip_atomic_fetch_max(&P.ws->idx_bad, (u64)P.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  (void)P;
+  Workspace* ws = KARGP(Workspace*, ws);
+  const u32 epoch = KARG32(epoch);
+  u64 word = ((u64)epoch << 8) | ((u64)(u32)(-code) << 4) | (u64)(detail & 15u);
+  __hip_atomic_fetch_max(&ws->err, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (KARG32(index_call)) __hip_atomic_fetch_max(&ws->idx_bad, (u64)epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- decoupled look-back over the sizes of the outgoing chunks (first wavefront, all 64 lanes) ----
@@ -202,7 +226,7 @@ __device__ __forceinline__ void publish_size(u64* stat, u32 c, u64 mine, u32 epo
 // (error raised).  Four windows of 64 status words are fetched per round trip.
 __device__ __forceinline__ bool lookback(u64* stat, u32 c, u64 mine, const Params& P, u64& excl_out) {
   const u32 lane = threadIdx.x & 63u;
-  const u64 tag = (u64)P.scan_epoch << kEpochShift;
+  const u64 tag = (u64)KARG32(scan_epoch) << kEpochShift;
   u64 excl = 0;
   if (c > 0) {
     long long look = (long long)c - 1;
@@ -220,10 +244,13 @@ __device__ __forceinline__ bool lookback(u64* stat, u32 c, u64 mine, const Param
         }
         if (__ballot(!ready) == 0) break;
         ++polls;
-        if ((polls & 63u) == 0 || polls >= P.spin_limit) {
-          const bool stop = polls >= P.spin_limit || ld_dev(&P.ws->abort) == (u64)P.epoch;
+        const u32 spin_limit = KARG32(spin_limit);
+        if ((polls & 63u) == 0 || polls >= spin_limit) {
+          Workspace* ws = KARGP(Workspace*, ws);
+          const u64 epoch = KARG32(epoch);
+          const bool stop = polls >= spin_limit || ld_dev(&ws->abort) == epoch;
           if (stop) {                                   // uniform: every lane reads the same words
-            if (lane == 0) { st_dev(&P.ws->abort, (u64)P.epoch); raise_error(P, CCOLL_ETIMEDOUT, 8); }
+            if (lane == 0) { st_dev(&ws->abort, epoch); raise_error(P, CCOLL_ETIMEDOUT, 8); }
             excl_out = 0;
             return false;
           }
@@ -1061,7 +1088,7 @@ struct SrcReduce {                                    // reduce step: local floa
   }
   template <bool FULL>
   __device__ __forceinline__ void load(const Params& P, u32 c, int u, u32 (&xb)[kE], int& nv, int& blen) const {
-    load_unit<FULL>(local, P.n, c, u, al, xb, nv, blen);
+    load_unit<FULL>(KARGP(const float*, local), FULL ? 0ull : KARG64(n), c, u, al, xb, nv, blen);
   }
   // bodies of unit u of the incoming chunk: payload bytes [ustart, uend)
   __device__ __forceinline__ void unit_span(const Params& P, u32 c, int u, u32& ustart, u32& uend) const {
@@ -1421,13 +1448,13 @@ __device__ __forceinline__ ChunkOut encode_chunk(Src& src, u32 c, const Params& 
 
 // Header of the stream: written by the wavefront that places the last chunk.
 __device__ __forceinline__ void write_header(const Params& P, u64 total) {
-  u32* h = (u32*)P.out;
+  u32* h = KARGP(u32*, out);
   h[0] = 0x31585343u;               // 'C','S','X','1'
   h[1] = (u32)kBlock | ((u32)kChunk << 16);
   h[2] = (u32)P.n; h[3] = (u32)(P.n >> 32);
-  h[4] = P.eb_bits; h[5] = P.nchunks;
+  h[4] = KARG32(eb_bits); h[5] = KARG32(nchunks);
   h[6] = (u32)total; h[7] = (u32)(total >> 32);
-  st_dev(&P.ws->total, total);
+  st_dev(&KARGP(Workspace*, ws)->total, total);
 }
 
 // The payload of chunk c, still in LDS stage L (and, what had outgrown it, in the spill slot), goes to its place.
@@ -1435,16 +1462,18 @@ template <u32 CAP>
 __device__ __forceinline__ void place_staged(u32 c, const ChunkOut& o, u64 off, const unsigned char* slot, const Params& P,
                                              EncWaveLds<CAP>& L) {
   const u32 lane = threadIdx.x & 63u;
-  const u64 front = kHeader + 4ull * P.nchunks;
-  const bool fits = front + off + o.payload <= P.out_cap;
+  const u32 nchunks = KARG32(nchunks), c1 = KARG32(c1);
+  const u64 front = kHeader + 4ull * nchunks;
+  const bool fits = front + off + o.payload <= KARG64(out_cap);
   if (lane == 0) {
     if (!fits) raise_error(P, CCOLL_ENOSPC);
-    if (c + 1 == P.nchunks) write_header(P, front + off + o.payload);
-    else if (c + 1 == P.c1) st_dev(&P.ws->total, front + off + o.payload);      // a piece of a stream: bytes so far
-    if (c + 1 == P.c1 && P.progress) { P.progress[0] = P.c1; P.progress[1] = front + off + o.payload; }
+    if (c + 1 == nchunks) write_header(P, front + off + o.payload);
+    else if (c + 1 == c1) st_dev(&KARGP(Workspace*, ws)->total, front + off + o.payload);      // a piece of a stream: bytes so far
+    unsigned long long* progress = KARGP(unsigned long long*, progress);
+    if (c + 1 == c1 && progress) { progress[0] = c1; progress[1] = front + off + o.payload; }
   }
   if (!fits) return;
-  unsigned char* dst = (unsigned char*)P.out + front + off;
+  unsigned char* dst = KARGP(unsigned char*, out) + front + off;
   copy_out<false>(dst, (unsigned char*)L.meta, o.meta_len);
   if (o.flushed) copy_gg(dst + o.meta_len, slot + kMetaMax, o.flushed);
   copy_out<true>(dst + o.meta_len + o.flushed, L.body, pad4(o.bodies) - o.flushed);
@@ -1468,23 +1497,23 @@ struct GroupLds {
 template <int NW, u32 CAP, class Src>
 __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLds<NW>& g, EncWaveLds<CAP>* Ls, u32 slot_bytes) {
   const u32 lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
-  unsigned char* gout = (unsigned char*)P.out;
   const u32 nfull = (u32)(P.n / kChunk);
-  const u32 g0 = P.c0 / NW;                                   // the launch codes chunks [c0, c1): groups [g0, ngroups)
-  const u32 ngroups = (P.c1 + NW - 1) / NW;
+  const u32 g0 = KARG32(c0) / NW;                             // the launch codes chunks [c0, c1): groups [g0, ngroups)
+  const u32 ngroups = (KARG32(c1) + NW - 1) / NW;
   const GrpMasks gm = grp_masks();
   // two spill slots per wavefront, used in turns: one may still hold the parked payload of the previous turn
   // while the chunk being coded outgrows the LDS stage into the other
-  unsigned char* slots = P.spill + ((u64)blockIdx.x * NW + wv) * 2u * slot_bytes;
+  const u64 slot0 = ((u64)blockIdx.x * NW + wv) * 2u * slot_bytes;          // + the spill area's base (a parameter read where used)
 
   // bodies are ORed into the stages: they start as zeros, and every copy out of a stage leaves zeros behind
 #pragma unroll
   for (int i = 0; i < 2; ++i)
     for (u32 j = lane; j < (CAP + 16u) / 16u; j += 64u) *(uint4*)(Ls[i].body + 16u * j) = make_uint4(0, 0, 0, 0);
-  u64* ticket = &P.ws->ticket[P.ticket_sel];
   if (threadIdx.x == 0) {
-    if (blockIdx.x == 0) st_dev(&P.ws->ticket[P.ticket_sel ^ 1u], 0ull);      // for the next launch on the stream
-    const u64 t = (u64)g0 + __hip_atomic_fetch_add(ticket, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    Workspace* ws = KARGP(Workspace*, ws);
+    const u32 sel = KARG32(ticket_sel);
+    if (blockIdx.x == 0) st_dev(&ws->ticket[sel ^ 1u], 0ull);                 // for the next launch on the stream
+    const u64 t = (u64)g0 + __hip_atomic_fetch_add(&ws->ticket[sel], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     g.next[1] = t < (u64)ngroups ? (u32)t : ngroups;
   }
   __syncthreads();
@@ -1495,15 +1524,17 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
   u32 turn = 0;
   for (; q < ngroups; ++turn) {
     const u32 par = turn & 1u, ts = turn % 3u, tp = (turn + 2u) % 3u;   // tp: the previous turn's sizes
+    unsigned char* slots = KARGP(unsigned char*, spill) + slot0;
     unsigned char* slot = slots + par * slot_bytes;           // this turn's
     unsigned char* pslot = slots + (par ^ 1u) * slot_bytes;   // the previous turn's
     EncWaveLds<CAP>& L = Ls[par];
     EncWaveLds<CAP>& Lp = Ls[par ^ 1u];                       // where the previous turn's payload is
     // the next group is asked for now, it is needed after the barrier
     u64 tnext = 0;
-    if (threadIdx.x == 0) tnext = (u64)g0 + __hip_atomic_fetch_add(ticket, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0)
+      tnext = (u64)g0 + __hip_atomic_fetch_add(&KARGP(Workspace*, ws)->ticket[KARG32(ticket_sel)], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const u32 c = q * NW + wv;
-    const bool have = c < P.c1;
+    const bool have = c < KARG32(c1);
     ChunkOut o; o.payload = 0; o.meta_len = 0; o.bodies = 0; o.flushed = 0;
     if (have) o = c < nfull ? encode_chunk<true, CAP>(src, c, P, gm, L, slot) : encode_chunk<false, CAP>(src, c, P, gm, L, slot);
     // The first wavefront walks the scan for the previous group's place while the slower wavefronts of the
@@ -1513,12 +1544,12 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
 #pragma unroll
       for (int j = 0; j < NW; ++j) ptot += g.size[tp][j];
       u64 pb = 0;
-      const bool pr = lookback(P.stat, pq, ptot, P, pb);
+      const bool pr = lookback(KARGP(u64*, stat), pq, ptot, P, pb);
       if (lane == 0) { g.pres[par] = pr ? 1u : 0u; g.pbase[par] = pb; }
     }
     if (lane == 0) {
       g.size[ts][wv] = o.payload;
-      if (have) ((u32*)(gout + kHeader))[c] = o.payload;       // the front index entry (Sec. III-E.2)
+      if (have) ((u32*)(KARGP(unsigned char*, out) + kHeader))[c] = o.payload;       // the front index entry (Sec. III-E.2)
     }
     if (threadIdx.x == 0) g.next[par] = tnext < (u64)ngroups ? (u32)tnext : ngroups;
     __syncthreads();
@@ -1526,7 +1557,7 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
       u32 gtot = 0;
 #pragma unroll
       for (int j = 0; j < NW; ++j) gtot += g.size[ts][j];
-      publish_size(P.stat, q, gtot, P.scan_epoch);
+      publish_size(KARGP(u64*, stat), q, gtot, KARG32(scan_epoch));
     }
     if (pend) {
       if (g.pres[par] == 0) { dead = true; break; }           // the scan wait was abandoned: error raised, everyone leaves
@@ -1546,14 +1577,14 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
 #pragma unroll
       for (int j = 0; j < NW; ++j) ptot += g.size[tp][j];
       u64 pb = 0;
-      const bool pr = lookback(P.stat, pq, ptot, P, pb);
+      const bool pr = lookback(KARGP(u64*, stat), pq, ptot, P, pb);
       if (lane == 0) { g.pres[par] = pr ? 1u : 0u; g.pbase[par] = pb; }
     }
     __syncthreads();
     if (g.pres[par] == 1 && phave) {
       u64 off = g.pbase[par];
       for (u32 j = 0; j < wv; ++j) off += g.size[tp][j];
-      place_staged<CAP>(pc, po, off, slots + (par ^ 1u) * slot_bytes, P, Ls[par ^ 1u]);
+      place_staged<CAP>(pc, po, off, KARGP(unsigned char*, spill) + slot0 + (par ^ 1u) * slot_bytes, P, Ls[par ^ 1u]);
     }
   }
 }
