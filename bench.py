@@ -4,9 +4,11 @@
 A step = one pass of the whole hot path over one synthetic field already resident in HBM:
 compress(x) -> decompress(stream) -> reduce_step(local, stream), all through the C ABI's enqueue-only
 calls on one stream.  `value` is uncompressed float32 bytes handled per second by the step
-(3 calls x 4n bytes / step time); the per-call rates (HIP events between the calls of the timed steps), the
-compression ratio and the roofline of the slowest call are in the same JSON line, next to the durations of
-the same calls launched 20 times in a row.  The CPU oracle is timed beside it on a bounded sample.
+(3 calls x 4n bytes / step time).  In the timed steps the library records HIP events around each coding / decoding
+kernel itself (`kernel_ms`; the roofline of the slowest kernel comes from these).  The per-call rates come from
+the same steps run once more with events recorded between the calls (a call = index scan + kernel + gaps + two
+event markers), next to the durations of the same calls launched 20 times in a row and the compression ratio.
+The CPU oracle is timed beside it on a bounded sample.
 
 Besides the headline line (the 512^3 field at relative bound 1e-3) the same JSON object carries, unless
 --no-extras is given, the other workloads of the benchmark spec: `ring8` (the per-rank compute of a compressed ring
@@ -55,6 +57,38 @@ def time_kernel(torch, fn, reps: int) -> float:
     e1.record()
     e1.synchronize()
     return e0.elapsed_time(e1) / reps
+
+
+class KernelTimer:
+    """Pairs of HIP events that the library records around a kernel itself (ccoll_time_next_kernel): the
+    dispatch's own start and end, without the marker packets of events recorded between calls."""
+
+    def __init__(self):
+        import ctypes
+        self.ct = ctypes
+        self.hip = ctypes.CDLL("libamdhip64.so.7")     # the runtime the library is linked against (already loaded)
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.all = []
+
+    def pair(self):
+        evs = []
+        for _ in range(2):
+            e = self.ct.c_void_p()
+            rc = self.hip.hipEventCreate(self.ct.byref(e)); assert rc == 0, rc
+            evs.append(e.value); self.all.append(e.value)
+        return tuple(evs)
+
+    def ms(self, pair) -> float:
+        out = self.ct.c_float()
+        rc = self.hip.hipEventElapsedTime(self.ct.byref(out), pair[0], pair[1]); assert rc == 0, rc
+        return out.value
+
+    def close(self):
+        for e in self.all:
+            self.hip.hipEventDestroy(e)
+        self.all = []
 
 
 def _cpu_model() -> str:
@@ -411,8 +445,8 @@ def bench_sweep(pkg, torch, workloads):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=100, help="untimed steps first (the device needs some tens of ms of work to reach its running clocks)")
     ap.add_argument("--workload", default="field512")
     ap.add_argument("--rel-eb", type=float, default=1e-3)
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="elements the oracle is timed on (0 = skip)")
@@ -462,23 +496,41 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # The timed region: K steps.  HIP events on the launch stream between the calls give each call's
-    # average duration inside that region (a call = its kernels: index scan + decode / fused kernel).
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    # The timed region: K steps.  The library records a pair of HIP events around each coding / decoding kernel
+    # itself, on the stream it launches on: the kernels' own durations inside the timed region.
+    kt = KernelTimer()
+    kev = [[kt.pair() for _ in range(3)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):
-        ev[k][0].record(); k_compress(); ev[k][1].record(); k_decompress(); ev[k][2].record(); k_reduce(); ev[k][3].record()
+        ctx.time_next_kernel(*kev[k][0]); k_compress()
+        ctx.time_next_kernel(*kev[k][1]); k_decompress()
+        ctx.time_next_kernel(*kev[k][2]); k_reduce()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / args.steps
+    kms = [sum(kt.ms(kev[k][i]) for k in range(args.steps)) / args.steps for i in range(3)]
+    kt.close()
+
+    # The same K steps once more with events recorded between the calls: each call's duration as its caller sees
+    # it (index scan + kernel + the gaps around them, and the two event markers).
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    for k in range(args.steps):
+        ev[k][0].record(); k_compress(); ev[k][1].record(); k_decompress(); ev[k][2].record(); k_reduce(); ev[k][3].record()
+    torch.cuda.synchronize()
     ms_c = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
     ms_d = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
     ms_r = sum(e[2].elapsed_time(e[3]) for e in ev) / args.steps
+    # and once more with no events at all
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step_plain = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # the same calls back to back (20 launches of one kind in a row), for comparison
     reps = max(5, args.steps)
-    b2b = {"k_compress": time_kernel(torch, k_compress, reps), "k_decompress": time_kernel(torch, k_decompress, reps),
-           "k_reduce_step": time_kernel(torch, k_reduce, reps)}
+    b2b = {"compress": time_kernel(torch, k_compress, reps), "decompress": time_kernel(torch, k_decompress, reps),
+           "reduce_step": time_kernel(torch, k_reduce, reps)}
 
     # a plain device copy of the same field on the same box, for scale (read + written bytes per second)
     ms_copy = time_kernel(torch, lambda: y.copy_(dx), reps)
@@ -491,7 +543,8 @@ def main():
         "k_decompress": cbytes + 4.0 * n,
         "k_reduce_step": 4.0 * n + cbytes + rbytes,
     }
-    dur = {"k_compress": ms_c, "k_decompress": ms_d, "k_reduce_step": ms_r}
+    dur = {"k_compress": kms[0], "k_decompress": kms[1], "k_reduce_step": kms[2]}       # the kernels themselves
+    call = {"compress": ms_c, "decompress": ms_d, "reduce_step": ms_r}                    # the calls, with event markers
     dom = max(dur, key=dur.get)
     achieved = alg[dom] / (dur[dom] * 1e-3) / 1e9
 
@@ -507,8 +560,11 @@ def main():
         "decompress_frac_hbm_peak": round(gb / (ms_d * 1e-3) / HBM_PEAK_GBPS, 4),
         "reduce_step_frac_hbm_peak": round(gb / (ms_r * 1e-3) / HBM_PEAK_GBPS, 4),
         "CR": round(cr, 3), "CR_reduce_out": round(cr2, 3), "max_abs_err_over_eb": round(err / eb, 4),
+        "ms_per_step_without_events": round(ms_step_plain, 4),
         "kernel_ms": {k: round(v, 4) for k, v in dur.items()},
-        "kernel_ms_back_to_back": {k: round(v, 4) for k, v in b2b.items()},
+        "kernel_frac_hbm_peak_uncompressed": {k: round(gb / (v * 1e-3) / HBM_PEAK_GBPS, 4) for k, v in dur.items()},
+        "call_ms_between_events": {k: round(v, 4) for k, v in call.items()},
+        "call_ms_back_to_back": {k: round(v, 4) for k, v in b2b.items()},
         "device_copy_rw_GBps": round(copy_rw, 1),
         "rw_frac_of_device_copy": {k: round(alg[k] / (dur[k] * 1e-3) / 1e9 / copy_rw, 4) for k in dur},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,

@@ -71,6 +71,13 @@ void ccoll_destroy(ccoll_ctx *ctx);
  * not valid).  polls = 0 restores the default (about a second).  Meant for tests of that path and for
  * callers that share the device with long-running kernels. */
 int  ccoll_set_scan_wait(ccoll_ctx *ctx, unsigned int polls);
+/* Measurement aid.  start_event / stop_event: two hipEvent_t created by the caller with timing enabled
+ * (either may be null).  The coding or decoding kernel of the next compress / decompress / reduce_step call on
+ * this context (not its index scan) is launched so that the events take the start and the end of that kernel
+ * itself; hipEventElapsedTime(start, stop), once stop has completed, is the kernel's duration without the gaps
+ * that events recorded around the call would include.  One call consumes the pair; a call that launches no
+ * such kernel (n == 0, a refused argument) leaves it armed. */
+int  ccoll_time_next_kernel(ccoll_ctx *ctx, void *start_event, void *stop_event);
 
 /* Upper bound of the stream size for n elements: 32 + ceil(n/5120) * 22052. */
 size_t ccoll_szx_max_compressed_bytes(size_t n);

@@ -19,6 +19,7 @@ _SIGNATURES = {
     "ccoll_reserve": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t]),
     "ccoll_destroy": (None, [ctypes.c_void_p]),
     "ccoll_set_scan_wait": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint]),
+    "ccoll_time_next_kernel": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
     "ccoll_szx_max_compressed_bytes": (ctypes.c_size_t, [ctypes.c_size_t]),
     "ccoll_szx_compress": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float,
                                           ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]),
@@ -185,6 +186,12 @@ class Context:
         rc = self._lib.ccoll_set_scan_wait(self._h, polls)
         if rc:
             raise CcollError(rc, "ccoll_set_scan_wait")
+
+    def time_next_kernel(self, start_event: int, stop_event: int):
+        """ccoll_time_next_kernel; the arguments are raw hipEvent_t handles (integers), 0 for none."""
+        rc = self._lib.ccoll_time_next_kernel(self._h, ctypes.c_void_p(start_event or None), ctypes.c_void_p(stop_event or None))
+        if rc:
+            raise CcollError(rc, "ccoll_time_next_kernel")
 
     # ---- waiting calls: return codes are raised as CcollError -------------------------------
     def compress(self, x, abs_eb: float, out=None) -> "torch.Tensor":

@@ -21,6 +21,7 @@
 // No MFMA: the path is a streaming codec bound by instruction issue and HBM, not by a contraction.
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <string.h>
 #include <math.h>
@@ -1688,6 +1689,7 @@ struct ccoll_ctx {
   const void* idx_ptr;    // the stream whose chunk offsets are in `offs` (ccoll_szx_index), or null
   size_t idx_bytes, idx_n;
   unsigned char* spill;   // device, one slot per wavefront of the widest ticketed launch
+  hipEvent_t ev_start, ev_stop;   // if set: recorded around the next coding / decoding kernel (ccoll_time_next_kernel)
 };
 
 namespace {
@@ -1701,6 +1703,18 @@ bool hip_ok(hipError_t e, const char* what) {
   return false;
 }
 #define HIP_OK(call) hip_ok((call), #call)
+
+// Launch of a call's coding / decoding kernel.  If the caller has armed a pair of events, they take the start and
+// the end of this dispatch itself (the dispatch packet's own time stamps: no marker packets around it).
+template <class K, class... Args>
+void launch_main(ccoll_ctx* c, K kernel, dim3 grid, dim3 block, Args... args) {
+  if (c->ev_start || c->ev_stop) {
+    hipExtLaunchKernelGGL(kernel, grid, block, 0, c->stream, c->ev_start, c->ev_stop, 0, args...);
+    c->ev_start = nullptr; c->ev_stop = nullptr;
+  } else {
+    hipLaunchKernelGGL(kernel, grid, block, 0, c->stream, args...);
+  }
+}
 
 int reset_workspace(ccoll_ctx* c) {
   if (!HIP_OK(hipMemsetAsync(c->ws, 0, sizeof(Workspace), c->stream))) return CCOLL_EHIP;
@@ -1773,7 +1787,7 @@ int ccoll_create(ccoll_ctx** out, int device, void* hip_stream) {
   ccoll_ctx* c = new (std::nothrow) ccoll_ctx();
   if (!c) return CCOLL_EHIP;
   c->device = device; c->stream = (hipStream_t)hip_stream; c->stat = nullptr; c->cap_chunks = 0;
-  c->ws = nullptr; c->spill = nullptr; c->spin_limit = kSpinLimit; c->idx_ptr = nullptr; c->idx_bytes = 0; c->idx_n = 0; c->host_ws = nullptr; c->offs = nullptr; c->last_epoch = 0; c->last_total = false; c->waited_epoch = 0; c->own_slot = 0; c->idx_epoch = 0; c->spill_waves = 0; c->pipe_open = false;
+  c->ws = nullptr; c->spill = nullptr; c->spin_limit = kSpinLimit; c->idx_ptr = nullptr; c->idx_bytes = 0; c->idx_n = 0; c->host_ws = nullptr; c->offs = nullptr; c->last_epoch = 0; c->last_total = false; c->waited_epoch = 0; c->own_slot = 0; c->idx_epoch = 0; c->spill_waves = 0; c->pipe_open = false; c->ev_start = nullptr; c->ev_stop = nullptr;
   if (!HIP_OK(hipMalloc((void**)&c->ws, sizeof(Workspace))) ||
       !HIP_OK(hipHostMalloc((void**)&c->host_ws, sizeof(Workspace), hipHostMallocDefault))) {
     ccoll_destroy(c); return CCOLL_EHIP;
@@ -1822,6 +1836,12 @@ int ccoll_reserve(ccoll_ctx* c, size_t max_n) {
   return HIP_OK(hipStreamSynchronize(c->stream)) ? CCOLL_OK : CCOLL_EHIP;
 }
 
+int ccoll_time_next_kernel(ccoll_ctx* c, void* start_event, void* stop_event) {
+  if (!c) return CCOLL_EINVAL;
+  c->ev_start = (hipEvent_t)start_event; c->ev_stop = (hipEvent_t)stop_event;
+  return CCOLL_OK;
+}
+
 int ccoll_set_scan_wait(ccoll_ctx* c, unsigned int polls) {
   if (!c) return CCOLL_EINVAL;
   c->spin_limit = polls ? polls : kSpinLimit;
@@ -1859,7 +1879,7 @@ int ccoll_szx_compress_async(ccoll_ctx* c, const float* d_in, size_t n, float ab
     const u32 ngroups = (P.nchunks + kEncWaves - 1) / kEncWaves;
     const u32 grid = grid_for(c->grid_compress, ngroups);
     P.ticket_sel = c->ticket_sel; c->ticket_sel ^= 1u; P.spill = c->spill;
-    hipLaunchKernelGGL(k_compress, dim3(grid), dim3(64 * kEncWaves), 0, c->stream, P);
+    launch_main(c, k_compress, dim3(grid), dim3(64 * kEncWaves), P);
   }
   return after_launch(c, P, d_result, true);
 }
@@ -1887,7 +1907,7 @@ int ccoll_szx_decompress_range_async(ccoll_ctx* c, const void* d_in, size_t in_b
   hipLaunchKernelGGL(k_index_scan, dim3((P.nchunks + kScanTile - 1) / kScanTile), dim3(1024), 0, c->stream, P);
   {
     u32 grid = (P.c1 - P.c0 + kDecWaves - 1) / kDecWaves;
-    hipLaunchKernelGGL(k_decompress, dim3(grid), dim3(64 * kDecWaves), 0, c->stream, P);
+    launch_main(c, k_decompress, dim3(grid), dim3(64 * kDecWaves), P);
   }
   return after_launch(c, P, d_result, false);
 }
@@ -1925,7 +1945,7 @@ int ccoll_szx_decompress_range_indexed_async(ccoll_ctx* c, const void* d_in, siz
   P.idx_epoch = c->idx_epoch;                  // an enqueue-only index call may still turn out to have failed
   if (n == 0 || count == 0) return after_launch(c, P, d_result, false);
   P.c0 = (u32)(first / kChunk); P.c1 = (u32)((first + count + kChunk - 1) / kChunk);
-  hipLaunchKernelGGL(k_decompress, dim3((P.c1 - P.c0 + kDecWaves - 1) / kDecWaves), dim3(64 * kDecWaves), 0, c->stream, P);
+  launch_main(c, k_decompress, dim3((P.c1 - P.c0 + kDecWaves - 1) / kDecWaves), dim3(64 * kDecWaves), P);
   return after_launch(c, P, d_result, false);
 }
 
@@ -1967,7 +1987,7 @@ int ccoll_szx_compress_chunks_async(ccoll_ctx* c, const float* d_in, size_t chun
   const u32 ngroups = (u32)((chunk_end + kEncWaves - 1) / kEncWaves - chunk_first / kEncWaves);
   const u32 grid = grid_for(c->grid_compress, ngroups);
   P.ticket_sel = c->ticket_sel; c->ticket_sel ^= 1u; P.spill = c->spill;
-  hipLaunchKernelGGL(k_compress, dim3(grid), dim3(64 * kEncWaves), 0, c->stream, P);
+  launch_main(c, k_compress, dim3(grid), dim3(64 * kEncWaves), P);
   rc = after_launch(c, P, d_result, true);
   if (rc) { c->pipe_open = false; return rc; }
   c->pipe_next = chunk_end;
@@ -1995,7 +2015,7 @@ int ccoll_szx_decompress_chunks_async(ccoll_ctx* c, const void* d_in, size_t in_
   P.scan_chunks = (u32)chunk_end; P.open_stream = 1;       // only what has arrived is checked; the total may not be final
   c->idx_ptr = nullptr;
   hipLaunchKernelGGL(k_index_scan, dim3((P.scan_chunks + kScanTile - 1) / kScanTile), dim3(1024), 0, c->stream, P);
-  hipLaunchKernelGGL(k_decompress, dim3((P.c1 - P.c0 + kDecWaves - 1) / kDecWaves), dim3(64 * kDecWaves), 0, c->stream, P);
+  launch_main(c, k_decompress, dim3((P.c1 - P.c0 + kDecWaves - 1) / kDecWaves), dim3(64 * kDecWaves), P);
   return after_launch(c, P, d_result, false);
 }
 
@@ -2046,7 +2066,7 @@ int ccoll_szx_decompress_ranges_async(ccoll_ctx* c, const void* d_in, size_t in_
       T.wg_end[k] = wgs;
     }
     T.nranges = k;
-    if (wgs) hipLaunchKernelGGL(k_decompress_ranges, dim3(wgs), dim3(64 * kDecWaves), 0, c->stream, P, T);
+    if (wgs) launch_main(c, k_decompress_ranges, dim3(wgs), dim3(64 * kDecWaves), P, T);
   }
   return after_launch(c, P, d_result, false);
 }
@@ -2079,9 +2099,9 @@ int ccoll_reduce_step_op_async(ccoll_ctx* c, int op, const float* d_local, size_
     const u32 ngroups = (P.nchunks + kRedWaves - 1) / kRedWaves;
     const u32 grid = grid_for(c->grid_reduce, ngroups);
     P.ticket_sel = c->ticket_sel; c->ticket_sel ^= 1u; P.spill = c->spill;
-    if (op == CCOLL_OP_MAX) hipLaunchKernelGGL(k_reduce_step_max, dim3(grid), dim3(64 * kRedWaves), 0, c->stream, P);
-    else if (op == CCOLL_OP_MIN) hipLaunchKernelGGL(k_reduce_step_min, dim3(grid), dim3(64 * kRedWaves), 0, c->stream, P);
-    else hipLaunchKernelGGL(k_reduce_step, dim3(grid), dim3(64 * kRedWaves), 0, c->stream, P);
+    if (op == CCOLL_OP_MAX) launch_main(c, k_reduce_step_max, dim3(grid), dim3(64 * kRedWaves), P);
+    else if (op == CCOLL_OP_MIN) launch_main(c, k_reduce_step_min, dim3(grid), dim3(64 * kRedWaves), P);
+    else launch_main(c, k_reduce_step, dim3(grid), dim3(64 * kRedWaves), P);
   }
   return after_launch(c, P, d_result, true);
 }
