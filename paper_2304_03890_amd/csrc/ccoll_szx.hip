@@ -859,7 +859,7 @@ __device__ __forceinline__ bool parse_meta(const unsigned char* st, u32 payload,
   if (meta > payload) bad = true;
   const bool in = (int)lane < nbc && !bad;
   const bool nonconst = in && ((bitmap >> lane) & 1ull);
-  const u32 rank = (u32)__popcll(bitmap & ((1ull << lane) - 1ull));
+  const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(bitmap >> 32), __builtin_amdgcn_mbcnt_lo((u32)bitmap, 0u));   // set bits below the lane's
   u32 bs = 0, rq = 0;
   if (nonconst) {
     bs = lds_load16(st + 8 + 4 * nbc + 2 * rank);
@@ -1497,7 +1497,7 @@ struct GroupLds {
 // One barrier per turn.  slot_bytes: size of a spill slot; every wavefront has two, used in turns.
 template <int NW, u32 CAP, class Src>
 __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLds<NW>& g, EncWaveLds<CAP>* Ls, u32 slot_bytes) {
-  const u32 lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
+  const u32 lane = threadIdx.x & 63u, wv = (u32)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // a scalar
   const u32 nfull = (u32)(P.n / kChunk);
   const u32 g0 = KARG32(c0) / NW;                             // the launch codes chunks [c0, c1): groups [g0, ngroups)
   const u32 ngroups = (KARG32(c1) + NW - 1) / NW;
@@ -1601,7 +1601,7 @@ struct __align__(16) CompressSmem { EncWaveLds<kEncCap> wave[kEncWaves][2]; Grou
 __global__ void __launch_bounds__(64 * kEncWaves) __attribute__((amdgpu_waves_per_eu(3, 3))) k_compress(Params P) {
   __shared__ CompressSmem sm;
   SrcPlain src; src.in = (const float*)P.in; src.al = P.aligned16 != 0;
-  encode_groups<kEncWaves, kEncCap>(src, P, sm.g, sm.wave[threadIdx.x >> 6], kSpillSlot);
+  encode_groups<kEncWaves, kEncCap>(src, P, sm.g, sm.wave[__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))], kSpillSlot);
 }
 
 // reduce step: 4 wavefronts per workgroup, three workgroups per compute unit; two stages per wavefront like
@@ -1616,7 +1616,7 @@ static_assert(kMetaMax + kBpc * kMaxBody + 16 <= kSpillSlot && kRedCap >= 8 * kM
 
 template <int OP>
 __device__ __forceinline__ void reduce_step_body(const Params& P, ReduceSmem& sm) {
-  const u32 wv = threadIdx.x >> 6;
+  const u32 wv = (u32)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   SrcReduce<OP, kRedCap> src; src.local = P.local; src.al = P.aligned16 != 0; src.s = (const unsigned char*)P.cin;
   src.stage = nullptr; src.src = nullptr; src.payload = 0; src.wbase = 0; src.wlen = 0; src.wpos = 0; src.good = false;
   encode_groups<kRedWaves, kRedCap>(src, P, sm.g, sm.wave[wv], kSpillSlot);
