@@ -187,6 +187,16 @@ __device__ __forceinline__ float u2f(u32 u) { return __uint_as_float(u); }
 __device__ __forceinline__ u32 bswap32(u32 v) { return __builtin_amdgcn_perm(0u, v, 0x00010203u); }
 __device__ __forceinline__ u32 pad4(u32 v) { return (v + 3u) & ~3u; }
 
+// Selection by a lane mask (all ones / all zeros) that the compiler cannot see through: it stays a bit operation.
+// A select would become v_cndmask_b32 in its short encoding, which this device issues six times slower than
+// other vector instructions (measured: 23 cycles per wavefront instruction against 3 to 4).
+__device__ __forceinline__ u32 lane_mask(bool c) { u32 m = c ? ~0u : 0u; asm("" : "+v"(m)); return m; }
+__device__ __forceinline__ u32 sel_mask(u32 m, u32 a, u32 b) {      // m ? a : b bit by bit, as one v_bitop3_b32 (the fast class)
+  u32 r;
+  asm("v_bitop3_b32 %0, %1, %2, %3 bitop3:0xca" : "=v"(r) : "v"(m), "v"(a), "v"(b));
+  return r;
+}
+
 __device__ __forceinline__ void lds_store16(unsigned char* p, u32 v) { unsigned short s = (unsigned short)v; __builtin_memcpy(p, &s, 2); }
 __device__ __forceinline__ void lds_store32(unsigned char* p, u32 v) { __builtin_memcpy(p, &v, 4); }
 __device__ __forceinline__ u32 lds_load32(const unsigned char* p) { u32 v; __builtin_memcpy(&v, p, 4); return v; }
@@ -351,10 +361,11 @@ __device__ __forceinline__ void enc_code(const u32 (&xb)[kE], int nv, const RowC
   const u32 half = raw ? 0u : (1u << (22 - m));
   const u32 sh = raw ? 0u : (23 - m);
   const float mu = rc.mu;
+  const u32 rawm = MAYRAW ? lane_mask(raw) : 0u;
 #pragma unroll
   for (int k = 0; k < kE; ++k) {
     const float v = __fsub_rn(u2f(xb[k]), mu);
-    const u32 src = raw ? xb[k] : f2u(v);
+    const u32 src = MAYRAW ? sel_mask(rawm, xb[k], f2u(v)) : f2u(v);
     r.t[k] = (src + half) >> sh;
   }
   u32 prev = grp_left(r.t[kE - 1], gm);         // last element of the lane to the left, 0 at the block start
@@ -532,44 +543,33 @@ __device__ __forceinline__ u32 dec_rows(int nv, int blen, const unsigned char* s
 // instead of four separate 16-byte pieces: whole 64-byte lines per instruction, which is what the memory
 // system wants (16 bytes per lane at a 64-byte stride ran at two thirds of the speed).  Two butterfly
 // stages of DPP moves and selects.  All four lanes of a quad must be active.
-// One butterfly stage for two vectors (4 dwords each): k = keep ? own : partner's, where the partner is the
-// lane CTRL away.  v_cndmask with a DPP source does select and lane exchange in one instruction (the compiler
-// does not fold the two); the s_nop covers the wait states a DPP read needs behind a VALU write of its source (2)
-// and behind a write of EXEC (5): the compiler's hazard recogniser does not look into the block.
-//   lo[d] <- keepmask ? lo[d] : partner's hi[d]        hi[d] <- keepmask ? partner's lo[d] : hi[d]
-#define CCOLL_BUTTERFLY(PERM, KEEP_LO, KEEP_HI, o0, o1, i0, i1)                                                     \
-  asm volatile("s_nop 4\n"                                                                                            \
-               "s_mov_b64 vcc, %[klo]\n"                                                                              \
-               "v_cndmask_b32_dpp %[a0], %[h0], %[l0], vcc " PERM " row_mask:0xf bank_mask:0xf\n"                     \
-               "v_cndmask_b32_dpp %[a1], %[h1], %[l1], vcc " PERM " row_mask:0xf bank_mask:0xf\n"                     \
-               "v_cndmask_b32_dpp %[a2], %[h2], %[l2], vcc " PERM " row_mask:0xf bank_mask:0xf\n"                     \
-               "v_cndmask_b32_dpp %[a3], %[h3], %[l3], vcc " PERM " row_mask:0xf bank_mask:0xf\n"                     \
-               "s_mov_b64 vcc, %[khi]\n"                                                                              \
-               "v_cndmask_b32_dpp %[b0], %[l0], %[h0], vcc " PERM " row_mask:0xf bank_mask:0xf\n"                     \
-               "v_cndmask_b32_dpp %[b1], %[l1], %[h1], vcc " PERM " row_mask:0xf bank_mask:0xf\n"                     \
-               "v_cndmask_b32_dpp %[b2], %[l2], %[h2], vcc " PERM " row_mask:0xf bank_mask:0xf\n"                     \
-               "v_cndmask_b32_dpp %[b3], %[l3], %[h3], vcc " PERM " row_mask:0xf bank_mask:0xf\n"                     \
-               : [a0] "=&v"(o0[0]), [a1] "=&v"(o0[1]), [a2] "=&v"(o0[2]), [a3] "=&v"(o0[3]),                          \
-                 [b0] "=&v"(o1[0]), [b1] "=&v"(o1[1]), [b2] "=&v"(o1[2]), [b3] "=&v"(o1[3])                           \
-               : [l0] "v"(i0[0]), [l1] "v"(i0[1]), [l2] "v"(i0[2]), [l3] "v"(i0[3]),                                  \
-                 [h0] "v"(i1[0]), [h1] "v"(i1[1]), [h2] "v"(i1[2]), [h3] "v"(i1[3]),                                  \
-                 [klo] "s"(KEEP_LO), [khi] "s"(KEEP_HI)                                                               \
-               : "vcc")
+// One butterfly stage for a pair of vectors (lo, hi) between a lane and its partner (the lane CTRL away): the
+// lanes with `first` set keep lo and hand over hi, the others keep hi and hand over lo, so one value per dword
+// crosses (one DPP move); the three selections are bit operations under a lane mask.
+template <int CTRL>
+__device__ __forceinline__ void butterfly(u32 first, u32 (&lo)[4], u32 (&hi)[4]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const u32 send = sel_mask(first, hi[d], lo[d]);
+    const u32 got = (u32)__builtin_amdgcn_update_dpp(0, (int)send, CTRL, 0xf, 0xf, true);
+    const u32 nlo = sel_mask(first, lo[d], got), nhi = sel_mask(first, got, hi[d]);
+    lo[d] = nlo; hi[d] = nhi;
+  }
+}
 
 __device__ __forceinline__ void quad_transpose(u32 (&x)[kE]) {
-  const u64 even = 0x5555555555555555ull, odd = 0xaaaaaaaaaaaaaaaaull;   // lanes with (lane & 1) == 0 / != 0
-  const u64 low2 = 0x3333333333333333ull, high2 = 0xccccccccccccccccull; // lanes with (lane & 2) == 0 / != 0
-  u32 v[4][4], a[4][4];
+  const u32 even = lane_mask((threadIdx.x & 1u) == 0), low2 = lane_mask((threadIdx.x & 2u) == 0);
+  u32 v[4][4];
 #pragma unroll
   for (int j = 0; j < 4; ++j)
 #pragma unroll
     for (int d = 0; d < 4; ++d) v[j][d] = x[4 * j + d];
-  // stage 1, partner lane ^ 1: a[2m] = even ? own 2m : partner's 2m+1;  a[2m+1] = odd ? own 2m+1 : partner's 2m
-  CCOLL_BUTTERFLY("quad_perm:[1,0,3,2]", even, odd, a[0], a[1], v[0], v[1]);
-  CCOLL_BUTTERFLY("quad_perm:[1,0,3,2]", even, odd, a[2], a[3], v[2], v[3]);
-  // stage 2, partner lane ^ 2: x[b] = low ? own b : partner's 2+b;  x[2+b] = high ? own 2+b : partner's b
-  CCOLL_BUTTERFLY("quad_perm:[2,3,0,1]", low2, high2, v[0], v[2], a[0], a[2]);
-  CCOLL_BUTTERFLY("quad_perm:[2,3,0,1]", low2, high2, v[1], v[3], a[1], a[3]);
+  // stage 1, partner lane ^ 1: even lanes end up with (own 2m, partner's 2m), odd lanes with (partner's 2m+1, own 2m+1)
+  butterfly<kQuadXor1>(even, v[0], v[1]);
+  butterfly<kQuadXor1>(even, v[2], v[3]);
+  // stage 2, partner lane ^ 2, on the vector pairs (b, 2 + b)
+  butterfly<kQuadXor2>(low2, v[0], v[2]);
+  butterfly<kQuadXor2>(low2, v[1], v[3]);
 #pragma unroll
   for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -1149,8 +1149,14 @@ struct SrcReduce {                                    // reduce step: local floa
     if (__ballot(rowbad != 0) != 0 && lane == 0) raise_error(P, CCOLL_ECORRUPT, 7);
     const bool use = good && !rowbad;
     if (OP == CCOLL_OP_SUM) {
+      if (__ballot(!use) == 0) {
 #pragma unroll
-      for (int k = 0; k < kE; ++k) xb[k] = f2u(__fadd_rn(u2f(xb[k]), use ? u2f(xo[k]) : 0.0f));
+        for (int k = 0; k < kE; ++k) xb[k] = f2u(__fadd_rn(u2f(xb[k]), u2f(xo[k])));
+      } else {
+        const u32 um = lane_mask(use);
+#pragma unroll
+        for (int k = 0; k < kE; ++k) xb[k] = f2u(__fadd_rn(u2f(xb[k]), u2f(xo[k] & um)));
+      }
     } else if (use) {
       // Max / Min (Sec. III-B) under the total order of the bit patterns: key = bits with the sign bit set for
       // non-negative values and all bits flipped for negative ones; the larger / smaller key wins.
@@ -1345,37 +1351,52 @@ __device__ __forceinline__ void flush_stage(EncWaveLds<CAP>& L, u32 bodybase, u3
   flushed += n;
 }
 
+// Where the bodies of a unit's blocks go: scans of the emitted bytes over the block and of the body sizes over the
+// wavefront, room made in the stage, mu and sizes noted for the chunk's metadata.  len: bytes the lane emits
+// (0 if its block is not active); v: body bytes of the block at its last lane, else 0.
+struct UnitPos { u32 incl, nlead, start, total; };
 template <bool FULL, u32 CAP, class Src>
-__device__ __forceinline__ u32 encode_unit(const u32 (&xb)[kE], int nv, int blen, int blk, int nbc, const Params& P,
-                                           const GrpMasks& gm, EncWaveLds<CAP>& L, u32 bodybase, u32& flushed, unsigned char* slot,
-                                           Src& src) {
-  const u32 lane = threadIdx.x & 63u, l8 = lane & 7u;
-  const bool exists = FULL || blen > 0;
-  const RowClass rc = classify_row(xb, P.eb, P.e_eb);
-  EncRegs r;
-  r.active = exists && rc.type != 0;
-  r.anyraw = __ballot(rc.type == 2) != 0;
-  if (r.anyraw) enc_code<FULL, true>(xb, nv, rc, gm, r);
-  else enc_code<FULL, false>(xb, nv, rc, gm, r);
-  if (!r.active) r.len = 0;
-  r.incl = grp_scan_add(r.len, gm);
-  r.nlead = FULL ? 32u : (u32)((blen + 3) >> 2);
-  const u32 v = (l8 == kGrp - 1 && r.active) ? r.nlead + r.incl : 0u;     // the block's body bytes, at its last lane
+__device__ __forceinline__ UnitPos place_unit(u32 len, bool active, int blen, int blk, int nbc, const RowClass& rc,
+                                              const GrpMasks& gm, EncWaveLds<CAP>& L, u32 bodybase, u32& flushed,
+                                              unsigned char* slot, Src& src) {
+  const u32 l8 = threadIdx.x & 7u;
+  UnitPos o;
+  o.incl = grp_scan_add(len, gm);
+  o.nlead = FULL ? 32u : (u32)((blen + 3) >> 2);
+  const u32 v = (l8 == kGrp - 1 && active) ? o.nlead + o.incl : 0u;       // the block's body bytes, at its last lane
   const u32 sc = wave_scan_add(v);
-  const u32 total = (u32)__builtin_amdgcn_readlane((int)sc, 63);
-  if (bodybase - flushed + total > CAP) flush_stage<CAP>(L, bodybase, flushed, slot);   // make room: at most 15 + 8 * 544 bytes are needed
-  src.make_room(bodybase - flushed + total);                              // a window of the source in the way is given up
-  const u32 start = bodybase - flushed + sc - v;                          // in the stage; the same for all lanes of a block
+  o.total = (u32)__builtin_amdgcn_readlane((int)sc, 63);
+  if (bodybase - flushed + o.total > CAP) flush_stage<CAP>(L, bodybase, flushed, slot);   // make room: at most 15 + 8 * 544 bytes are needed
+  src.make_room(bodybase - flushed + o.total);                            // a window of the source in the way is given up
+  o.start = bodybase - flushed + sc - v;                                  // in the stage; the same for all lanes of a block
   if (l8 == kGrp - 1 && blk < nbc) {
     L.meta[2 + blk] = f2u(rc.mu);
     L.tmp[blk] = v | ((rc.type == 0 ? 0u : (rc.type == 2 ? 32u : 9u + rc.m)) << 16);
   }
-  if (r.active) {
-    if (r.anyraw) write_body<FULL, true, false>(r, L.body + start);
-    else if (__ballot(r.nb != 2u) == 0) write_body_or<FULL, true>(r, (u32*)L.body, start);     // active lanes only
-    else write_body_or<FULL, false>(r, (u32*)L.body, start);
+  return o;
+}
+
+template <bool FULL, u32 CAP, class Src>
+__device__ __forceinline__ u32 encode_unit(const u32 (&xb)[kE], int nv, int blen, int blk, int nbc, const Params& P,
+                                           const GrpMasks& gm, EncWaveLds<CAP>& L, u32 bodybase, u32& flushed, unsigned char* slot,
+                                           Src& src) {
+  const bool exists = FULL || blen > 0;
+  const RowClass rc = classify_row(xb, P.eb, P.e_eb);
+  const bool active = exists && rc.type != 0;
+  const bool anyraw = __ballot(rc.type == 2) != 0;
+  EncRegs r;
+  r.active = active; r.anyraw = anyraw;
+  if (anyraw) enc_code<FULL, true>(xb, nv, rc, gm, r);
+  else enc_code<FULL, false>(xb, nv, rc, gm, r);
+  if (!active) r.len = 0;
+  const UnitPos o = place_unit<FULL, CAP>(r.len, active, blen, blk, nbc, rc, gm, L, bodybase, flushed, slot, src);
+  r.incl = o.incl; r.nlead = o.nlead;
+  if (active) {
+    if (anyraw) write_body<FULL, true, false>(r, L.body + o.start);
+    else if (__ballot(r.nb != 2u) == 0) write_body_or<FULL, true>(r, (u32*)L.body, o.start);     // active lanes only
+    else write_body_or<FULL, false>(r, (u32*)L.body, o.start);
   }
-  return total;
+  return o.total;
 }
 
 // A coded chunk: payload bytes, metadata bytes, body bytes, and how many of the body bytes are in the spill
@@ -1383,15 +1404,21 @@ __device__ __forceinline__ u32 encode_unit(const u32 (&xb)[kE], int nv, int blen
 struct ChunkOut { u32 payload, meta_len, bodies, flushed; };
 
 // Chunk c into the wavefront's LDS (and, if it outgrows the stage, its spill slot).
-template <bool FULL, u32 CAP, class Src>
+// xa / nv / blen: the floats of the chunk's first unit if `preloaded` (requested by the previous turn), else they are
+// loaded here.  `turn` is called between the units (the work a wavefront does for its workgroup while it codes) and
+// names, in front of the last unit, the chunk the wavefront codes next: a source that requests its elements a unit
+// ahead then requests that chunk's first unit, so that the turn after this one starts without a memory round trip
+// (on return `preloaded` says whether xa holds it).
+template <bool FULL, u32 CAP, class Src, class Turn>
 __device__ __forceinline__ ChunkOut encode_chunk(Src& src, u32 c, const Params& P, const GrpMasks& gm, EncWaveLds<CAP>& L,
-                                                 unsigned char* slot) {
+                                                 unsigned char* slot, u32 (&xa)[kE], int& nv, int& blen, bool& preloaded,
+                                                 Turn& turn) {
   const u32 lane = threadIdx.x & 63u;
   const int nbc = FULL ? kBpc : (int)((P.n - (u64)c * kChunk + kBlock - 1) / kBlock);
   const int nunits = FULL ? kUnits : (nbc + 7) / 8;
   src.begin_chunk(c, P, L.body);
-  u32 xa[kE]; int nv, blen;
-  src.template load<FULL>(P, c, 0, xa, nv, blen);
+  if (!(Src::kPrefetch && preloaded)) src.template load<FULL>(P, c, 0, xa, nv, blen);
+  preloaded = false;
   u32 bodybase = 0, flushed = 0;
 #pragma unroll 1
   for (int u = 0; u < nunits; ++u) {
@@ -1407,15 +1434,24 @@ __device__ __forceinline__ ChunkOut encode_chunk(Src& src, u32 c, const Params& 
       else __builtin_amdgcn_s_setprio(0);
     }
     if (Src::kPrefetch) {
+      // The floats of the next unit are requested now and taken over behind the coding of this one.  In front of the
+      // chunk's last unit the request is for the first unit of the chunk the wavefront codes next (if that is a whole
+      // chunk; else this chunk's first unit once more, unused: every pass requests and takes over the same way).
       u32 xn[kE]; int nvn = 0, blenn = 0;
-      if (u + 1 < nunits) src.template load<FULL>(P, c, u + 1, xn, nvn, blenn);     // in flight while this unit is coded
+      u32 cl = c; int ul = u + 1;
+      if (u + 1 == nunits) {
+        ul = 0;
+        if (FULL) {
+          const u32 cn = turn.next_chunk();
+          if (cn != ~0u) { cl = cn; preloaded = true; }
+        }
+      }
+      src.template load<FULL>(P, cl, ul, xn, nvn, blenn);
       src.template finish<FULL>(P, c, u, xa, nv, blen, gm);
       bodybase += encode_unit<FULL, CAP>(xa, nv, blen, blk, nbc, P, gm, L, bodybase, flushed, slot, src);
-      if (u + 1 < nunits) {
 #pragma unroll
-        for (int k = 0; k < kE; ++k) xa[k] = xn[k];
-        nv = nvn; blen = blenn;
-      }
+      for (int k = 0; k < kE; ++k) xa[k] = xn[k];
+      nv = nvn; blen = blenn;
     } else {
       if (u > 0) src.template load<FULL>(P, c, u, xa, nv, blen);
       if (src.needs_room(P, c, u, bodybase - flushed)) flush_stage<CAP>(L, bodybase, flushed, slot);
@@ -1423,7 +1459,9 @@ __device__ __forceinline__ ChunkOut encode_chunk(Src& src, u32 c, const Params& 
       src.template finish<FULL>(P, c, u, xa, nv, blen, gm);
       bodybase += encode_unit<FULL, CAP>(xa, nv, blen, blk, nbc, P, gm, L, bodybase, flushed, slot, src);
     }
+    turn.between_units(u);
   }
+  turn.after_units(nunits);
   src.end_chunk();
   if (Src::kPrefetch) __builtin_amdgcn_s_setprio(0);
   // metadata: lane j = block j
@@ -1486,7 +1524,60 @@ struct GroupLds {
                                                      // still read (offsets of parked payloads) during the next turn
   u64 pbase[2];                                      // byte offset of the parked group's first payload
   u32 pres[2];                                       // look-back result for it (1 known, 0 abandoned)
-  u32 next[2];                                       // the workgroup's next group
+  unsigned long long nextq[2];                       // by turn mod 2: (turn << 32) | the workgroup's group of the turn after
+  u32 first;                                         // the workgroup's first group
+};
+
+// What a wavefront does for its workgroup while it codes its chunk of the turn (called by encode_chunk between the
+// units).  The first wavefront hands on the ticket of the workgroup's next group as soon as it is there (after its
+// first unit), so that every wavefront knows in front of its last unit which chunk it codes next, and walks the
+// look-back scan for the group of the turn before when its own chunk is coded: by then the groups in front have,
+// as a rule, announced their sizes.  (Walking the scan earlier, between the units, was slower: 0.145 ms against
+// 0.141 ms on the 512^3 field; more of the walks then have to wait.)
+template <int NW>
+struct TurnWork {
+  GroupLds<NW>& g; const Params& P;
+  u32 wv, turn, ngroups, nfull;
+  bool pend; u32 pq;                                 // the group of the turn before waits for its place
+  u32 tnext;                                         // thread 0: the group drawn for the turn after this one (ngroups: none)
+  bool handed;
+  __device__ __forceinline__ void hand_on_ticket() {
+    if (threadIdx.x == 0)
+      __hip_atomic_store(&g.nextq[turn & 1u], ((unsigned long long)turn << 32) | tnext, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    handed = true;
+  }
+  __device__ __forceinline__ void between_units(int u) {
+    if (wv == 0 && u == 0) hand_on_ticket();
+  }
+  __device__ __forceinline__ void after_units(int) {
+    if (wv != 0) return;
+    if (!handed) hand_on_ticket();                   // a chunk without units cannot occur; kept for safety
+    if (pend) {
+      const u32 lane = threadIdx.x & 63u, par = turn & 1u, tp = (turn + 2u) % 3u;
+      u32 ptot = 0;
+#pragma unroll
+      for (int j = 0; j < NW; ++j) ptot += g.size[tp][j];
+      u64 pb = 0;
+      const bool pr = lookback(KARGP(u64*, stat), pq, ptot, P, pb);
+      if (lane == 0) { g.pres[par] = pr ? 1u : 0u; g.pbase[par] = pb; }
+    }
+  }
+  // The chunk this wavefront codes in the next turn if that is a whole chunk, else ~0.  The ticket has as a rule
+  // been handed on long ago; the wait is bounded, and giving up only costs the early request of the floats.
+  __device__ __forceinline__ u32 next_chunk() {
+    unsigned long long w = 0;
+    bool have = false;
+    for (int tries = 0; tries < 64 && !have; ++tries) {
+      w = __hip_atomic_load(&g.nextq[turn & 1u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      have = (u32)(w >> 32) == turn;
+      if (!have) __builtin_amdgcn_s_sleep(1);
+    }
+    if (!have) return ~0u;
+    const u32 qn = (u32)w;
+    if (qn >= ngroups) return ~0u;
+    const u32 cn = qn * NW + wv;
+    return (cn < nfull && cn < KARG32(c1)) ? cn : ~0u;
+  }
 };
 
 // Per turn a workgroup codes one group of NW chunks.  When a group has just been coded, the groups in front
@@ -1515,13 +1606,15 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
     const u32 sel = KARG32(ticket_sel);
     if (blockIdx.x == 0) st_dev(&ws->ticket[sel ^ 1u], 0ull);                 // for the next launch on the stream
     const u64 t = (u64)g0 + __hip_atomic_fetch_add(&ws->ticket[sel], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    g.next[1] = t < (u64)ngroups ? (u32)t : ngroups;
+    g.first = t < (u64)ngroups ? (u32)t : ngroups;
+    g.nextq[0] = ~0ull; g.nextq[1] = ~0ull;
   }
   __syncthreads();
-  u32 q = g.next[1];
+  u32 q = g.first;
   bool pend = false, phave = false, dead = false;
   u32 pq = 0, pc = 0;
   ChunkOut po; po.payload = 0; po.meta_len = 0; po.bodies = 0; po.flushed = 0;
+  u32 xa[kE]; int nv = 0, blen = 0; bool preloaded = false;    // the first unit of the next chunk, requested a turn ahead
   u32 turn = 0;
   for (; q < ngroups; ++turn) {
     const u32 par = turn & 1u, ts = turn % 3u, tp = (turn + 2u) % 3u;   // tp: the previous turn's sizes
@@ -1530,29 +1623,23 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
     unsigned char* pslot = slots + (par ^ 1u) * slot_bytes;   // the previous turn's
     EncWaveLds<CAP>& L = Ls[par];
     EncWaveLds<CAP>& Lp = Ls[par ^ 1u];                       // where the previous turn's payload is
-    // the next group is asked for now, it is needed after the barrier
-    u64 tnext = 0;
-    if (threadIdx.x == 0)
-      tnext = (u64)g0 + __hip_atomic_fetch_add(&KARGP(Workspace*, ws)->ticket[KARG32(ticket_sel)], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    TurnWork<NW> tw{g, P, wv, turn, ngroups, nfull, pend, pq, 0u, false};
+    // the next group is asked for now; the first wavefront hands it on while it codes
+    if (threadIdx.x == 0) {
+      const u64 t = (u64)g0 + __hip_atomic_fetch_add(&KARGP(Workspace*, ws)->ticket[KARG32(ticket_sel)], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      tw.tnext = t < (u64)ngroups ? (u32)t : ngroups;
+    }
     const u32 c = q * NW + wv;
     const bool have = c < KARG32(c1);
     ChunkOut o; o.payload = 0; o.meta_len = 0; o.bodies = 0; o.flushed = 0;
-    if (have) o = c < nfull ? encode_chunk<true, CAP>(src, c, P, gm, L, slot) : encode_chunk<false, CAP>(src, c, P, gm, L, slot);
-    // The first wavefront walks the scan for the previous group's place while the slower wavefronts of the
-    // group still code, in front of the turn's barrier.
-    if (wv == 0 && pend) {
-      u32 ptot = 0;
-#pragma unroll
-      for (int j = 0; j < NW; ++j) ptot += g.size[tp][j];
-      u64 pb = 0;
-      const bool pr = lookback(KARGP(u64*, stat), pq, ptot, P, pb);
-      if (lane == 0) { g.pres[par] = pr ? 1u : 0u; g.pbase[par] = pb; }
-    }
+    if (have) {
+      if (c < nfull) o = encode_chunk<true, CAP>(src, c, P, gm, L, slot, xa, nv, blen, preloaded, tw);
+      else { preloaded = false; o = encode_chunk<false, CAP>(src, c, P, gm, L, slot, xa, nv, blen, preloaded, tw); }
+    } else preloaded = false;
     if (lane == 0) {
       g.size[ts][wv] = o.payload;
       if (have) ((u32*)(KARGP(unsigned char*, out) + kHeader))[c] = o.payload;       // the front index entry (Sec. III-E.2)
     }
-    if (threadIdx.x == 0) g.next[par] = tnext < (u64)ngroups ? (u32)tnext : ngroups;
     __syncthreads();
     if (wv == 0) {                                            // announce this group's size
       u32 gtot = 0;
@@ -1569,7 +1656,7 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
       }
     }
     pend = true; phave = have; pq = q; pc = c; po = o;
-    q = g.next[par];
+    q = (u32)g.nextq[par];
   }
   if (pend && !dead) {                                        // the last group of this workgroup is still parked
     const u32 par = turn & 1u, tp = (turn + 2u) % 3u;
