@@ -41,6 +41,7 @@ namespace {
 typedef uint32_t u32;
 typedef uint64_t u64;
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u_a4 __attribute__((ext_vector_type(4), aligned(4)));   // a vector at a 4-byte aligned address
 
 constexpr int kBlock = CCOLL_BLOCK_ELEMS;            // 128
 constexpr int kChunk = CCOLL_CHUNK_ELEMS;            // 5120
@@ -302,8 +303,10 @@ __device__ __forceinline__ RowClass classify_row(const u32 (&xb)[kE], float eb, 
 #pragma unroll
   for (int k = 1; k < kE; ++k) { smax = max(smax, (int)xb[k]); smin = min(smin, (int)xb[k]); umax = max(umax, xb[k]); }
   smax = grp_max_i32(smax); smin = grp_min_i32(smin); umax = grp_max_u32(umax);
-  const u32 mxb = smax >= 0 ? (u32)smax : (u32)smin;             // largest value
-  const u32 mnb = (umax & 0x80000000u) ? umax : (u32)smin;       // smallest value
+  // largest value: the signed maximum if it is not negative, else (all negative) the signed minimum; smallest
+  // value: the unsigned maximum if it has the sign bit, else the signed minimum.  Selected under sign masks.
+  const u32 mxb = sel_mask((u32)(smax >> 31), (u32)smin, (u32)smax);
+  const u32 mnb = sel_mask((u32)((int)umax >> 31), umax, (u32)smin);
   const bool nonfinite = (smax >= 0x7f800000) || (umax >= 0xff800000u);
   const float mx = u2f(mxb), mn = u2f(mnb);
   const float d = __fsub_rn(mx, mn);
@@ -518,11 +521,12 @@ __device__ __forceinline__ u32 dec_rows_impl(int nv, int blen, const unsigned ch
       Vp = dpp0<kRowShr4>(V) & gm.m4; Np = dpp0<kRowShr4>(N) & gm.m4; V |= Vp & ~N; N |= Np;
     }
     const u32 tin = grp_left(V, gm);                                // 0 at the block start
+    const u32 rawm = MAYRAW ? lane_mask(raw) : 0u;
 #pragma unroll
     for (int k = 0; k < kE; ++k) {
       const u32 own = KEEPMASK ? c8[k] : (MAYRAW ? (u32)((1ull << c8[k]) - 1ull) : ~(~0u << c8[k]));
       const u32 tt = (own & t[k]) | (~own & tin);
-      xo[k] = raw ? tt : f2u(__fadd_rn(u2f(tt << sh), mu));
+      xo[k] = MAYRAW ? sel_mask(rawm, tt, f2u(__fadd_rn(u2f(tt << sh), mu))) : f2u(__fadd_rn(u2f(tt << sh), mu));
     }
   }
   return grp_or_u32(rowbad);
@@ -846,7 +850,17 @@ __device__ __forceinline__ void fetch_window(const unsigned char* src, u32 from,
 }
 
 // Per-block metadata of a chunk, lane j = block j (lanes >= nbc hold zeros).
-struct ChunkMeta { u32 rq, bs, boff, end; float mu; };
+struct ChunkMeta {
+  u32 rq, bs, boff, end; float mu;
+  u32 packed;                                          // rq | bs << 6 | boff << 16: one word to hand to the block's lanes
+};
+// What lane `b` holds of a chunk's metadata, for the lanes of block b: two cross-lane reads (ds_bpermute is the most
+// expensive instruction of the decoder: 24 cycles per wavefront) instead of four.
+__device__ __forceinline__ void block_info(const ChunkMeta& m, int b, u32 wbase, BlockInfo& bi, float& mu) {
+  const u32 w = (u32)__shfl((int)m.packed, b);
+  bi.rq = w & 63u; bi.bs = (w >> 6) & 1023u; bi.boff = (w >> 16) - wbase;
+  mu = __shfl(m.mu, b);
+}
 
 // Parses the metadata at the start of a payload (in `st`).  Returns false (wave-uniform) if malformed.
 __device__ __forceinline__ bool parse_meta(const unsigned char* st, u32 payload, int nbc, ChunkMeta& m) {
@@ -872,6 +886,7 @@ __device__ __forceinline__ bool parse_meta(const unsigned char* st, u32 payload,
   const u32 bodies = (u32)__builtin_amdgcn_readlane((int)sc, 63);
   if (pad4(meta + bodies) != payload) bad = true;
   m.rq = bad ? 0u : rq; m.bs = bs; m.end = meta + sc; m.boff = meta + sc - bs;
+  m.packed = m.rq | (m.bs << 6) | (m.boff << 16);      // rq <= 32, bs <= 544, boff <= 22048
   return !bad;
 }
 
@@ -905,10 +920,8 @@ __device__ __forceinline__ void decompress_chunk(u32 c, const Params& P, const u
       fetch_window(src, wbase, len, w);
     }
     const int b = 8 * u + (int)(lane >> 3);
-    BlockInfo bi;
-    bi.rq = (u32)__shfl((int)m.rq, b); bi.bs = (u32)__shfl((int)m.bs, b);
-    bi.boff = (u32)__shfl((int)m.boff, b) - wbase;
-    const float mu = __shfl(m.mu, b);
+    BlockInfo bi; float mu;
+    block_info(m, b, wbase, bi, mu);
     int blen = kBlock, nv = kE;
     if (!FULL) {
       blen = clen - b * kBlock; blen = blen < 0 ? 0 : (blen > kBlock ? kBlock : blen);
@@ -1079,7 +1092,7 @@ struct SrcReduce {                                    // reduce step: local floa
     stage = stage_body;
     const InChunk cur = locate_chunk(s, c, P, 0u);
     good = cur.ok; src = cur.src; payload = cur.size; wbase = 0; wlen = 0; wpos = kEnd;
-    m.rq = 0; m.bs = 0; m.boff = 0; m.end = 0; m.mu = 0.0f;
+    m.rq = 0; m.bs = 0; m.boff = 0; m.end = 0; m.mu = 0.0f; m.packed = 0;
     if (!good) { if (lane == 0) raise_error(P, CCOLL_ECORRUPT, 4); return; }
     fetch_from(0, 0);
     const u64 cbeg = (u64)c * kChunk;
@@ -1139,9 +1152,7 @@ struct SrcReduce {                                    // reduce step: local floa
     float mu = 0.0f;
     const unsigned char* win = stage + wpos;
     if (good) {
-      bi.rq = (u32)__shfl((int)m.rq, b); bi.bs = (u32)__shfl((int)m.bs, b);
-      bi.boff = (u32)__shfl((int)m.boff, b) - wbase;
-      mu = __shfl(m.mu, b);
+      block_info(m, b, wbase, bi, mu);
       if (!FULL && blen == 0) bi.rq = 0;
     }
     u32 xo[kE];
@@ -1198,7 +1209,7 @@ __device__ __forceinline__ void write_body(const EncRegs& r, unsigned char* body
     else c = (r.cc >> (2 * k)) & 3u;
     if (MAYRAW) {
       if (c == 1) p[0] = (unsigned char)t;
-      if (c == 2 || c == 3) lds_store16(p, __builtin_amdgcn_perm(0u, t, c == 2 ? 0x0c0c0001u : 0x0c0c0102u));
+      if (c == 2 || c == 3) lds_store16(p, __builtin_amdgcn_perm(0u, t, 0x0c0c0001u + (c & 1u) * 0x0101u));   // bytes 1, 0 or 2, 1
       if (c == 3) p[2] = (unsigned char)t;
       if (c == 4) lds_store32(p, bswap32(t));
     } else if (NB2) {
@@ -1282,7 +1293,9 @@ __device__ __forceinline__ void write_body_or(const EncRegs& r, u32* body32, u32
 // ZERO: the LDS bytes are set to zero behind the copy (a stage must be all zeros before bodies are ORed into it).
 // Four vectors per lane are read before the first one is stored, so that a payload of up to 4 KB costs one
 // LDS round trip.
-template <bool ZERO>
+// STREAM: streaming (non-temporal) stores.  Not used for the outgoing stream: they gain 1.6 % in the coder, but the
+// stream then bypasses the memory-side cache, and a decoder that reads it next on the same device loses 15 %.
+template <bool ZERO, bool STREAM = false>
 __device__ __forceinline__ void copy_out(unsigned char* dst, unsigned char* src, u32 n) {
   const u32 lane = threadIdx.x & 63u;
   const u32 n16 = n >> 4;
@@ -1300,7 +1313,10 @@ __device__ __forceinline__ void copy_out(unsigned char* dst, unsigned char* src,
       const u32 j = j0 + lane + 64u * (u32)i;
       if (j < n16) {
         if (ZERO) *(uint4*)(src + 16u * j) = make_uint4(0, 0, 0, 0);
-        __builtin_memcpy(dst + 16u * j, &v[i], 16);
+        if (STREAM) {
+          v4u_a4 t; t.x = v[i].x; t.y = v[i].y; t.z = v[i].z; t.w = v[i].w;
+          __builtin_nontemporal_store(t, (v4u_a4*)(dst + 16u * j));
+        } else __builtin_memcpy(dst + 16u * j, &v[i], 16);
       }
     }
   }
