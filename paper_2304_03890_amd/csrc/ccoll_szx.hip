@@ -41,7 +41,6 @@ namespace {
 typedef uint32_t u32;
 typedef uint64_t u64;
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
-typedef unsigned int v4u_a4 __attribute__((ext_vector_type(4), aligned(4)));   // a vector at a 4-byte aligned address
 
 constexpr int kBlock = CCOLL_BLOCK_ELEMS;            // 128
 constexpr int kChunk = CCOLL_CHUNK_ELEMS;            // 5120
@@ -1293,9 +1292,9 @@ __device__ __forceinline__ void write_body_or(const EncRegs& r, u32* body32, u32
 // ZERO: the LDS bytes are set to zero behind the copy (a stage must be all zeros before bodies are ORed into it).
 // Four vectors per lane are read before the first one is stored, so that a payload of up to 4 KB costs one
 // LDS round trip.
-// STREAM: streaming (non-temporal) stores.  Not used for the outgoing stream: they gain 1.6 % in the coder, but the
-// stream then bypasses the memory-side cache, and a decoder that reads it next on the same device loses 15 %.
-template <bool ZERO, bool STREAM = false>
+// The stores to the outgoing stream are ordinary ones: streaming (non-temporal) stores gain 1.6 % in the coder, but
+// the stream then bypasses the memory-side cache, and a decoder that reads it next on the same device loses 15 %.
+template <bool ZERO>
 __device__ __forceinline__ void copy_out(unsigned char* dst, unsigned char* src, u32 n) {
   const u32 lane = threadIdx.x & 63u;
   const u32 n16 = n >> 4;
@@ -1313,10 +1312,7 @@ __device__ __forceinline__ void copy_out(unsigned char* dst, unsigned char* src,
       const u32 j = j0 + lane + 64u * (u32)i;
       if (j < n16) {
         if (ZERO) *(uint4*)(src + 16u * j) = make_uint4(0, 0, 0, 0);
-        if (STREAM) {
-          v4u_a4 t; t.x = v[i].x; t.y = v[i].y; t.z = v[i].z; t.w = v[i].w;
-          __builtin_nontemporal_store(t, (v4u_a4*)(dst + 16u * j));
-        } else __builtin_memcpy(dst + 16u * j, &v[i], 16);
+        __builtin_memcpy(dst + 16u * j, &v[i], 16);
       }
     }
   }
