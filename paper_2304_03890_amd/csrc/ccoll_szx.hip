@@ -1187,40 +1187,55 @@ struct SrcReduce {                                    // reduce step: local floa
   }
 };
 
-// Lead codes and differing bytes of the lane's elements into the block body at `body` (LDS or global).
-// NB2 (only without raw blocks): every block of the wavefront has 2-byte elements.
-template <bool FULL, bool MAYRAW, bool NB2>
-__device__ __forceinline__ void write_body(const EncRegs& r, unsigned char* body) {
+// Lead codes and differing bytes of the lane's elements into the block's body, for a wavefront with a raw block
+// (an element emits up to 4 bytes).  The scheme of write_body_or below with one change: v_alignbyte shifts by 0 to 3
+// bytes, so an element's c <= 4 bytes enter the string in two pushes, min(c, 2) bytes of t and the c - min(c, 2)
+// bytes above them.  Four elements are at most 16 bytes: four registers, five words touched.  (Byte stores under
+// predicates, the first version, cost four times the instructions.)
+template <bool FULL>
+__device__ __forceinline__ void write_body_or4(const EncRegs& r, u32* body32, u32 off) {
   const u32 l8 = threadIdx.x & 7u;
-  if (FULL) {
-    lds_store32(body + 4 * l8, r.lc);
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (4 * l8 + i < r.nlead) body[4 * l8 + i] = (unsigned char)(r.lc >> (8 * i));
-  }
-  unsigned char* p = body + r.nlead + (r.incl - r.len);
-#pragma unroll
-  for (int k = 0; k < kE; ++k) {
-    const u32 t = r.t[k];
-    u32 c;
-    if (MAYRAW) { c = r.nb - ((r.lc >> (2 * k)) & 3u); if (!FULL && k >= r.nv) c = 0; }
-    else c = (r.cc >> (2 * k)) & 3u;
-    if (MAYRAW) {
-      if (c == 1) p[0] = (unsigned char)t;
-      if (c == 2 || c == 3) lds_store16(p, __builtin_amdgcn_perm(0u, t, 0x0c0c0001u + (c & 1u) * 0x0101u));   // bytes 1, 0 or 2, 1
-      if (c == 3) p[2] = (unsigned char)t;
-      if (c == 4) lds_store32(p, bswap32(t));
-    } else if (NB2) {
-      // c is 0, 1 or 2: one bit of its field decides each store (two independent tests, no nesting)
-      if (r.cc & (1u << (2 * k))) p[0] = (unsigned char)t;
-      if (r.cc & (2u << (2 * k))) lds_store16(p, __builtin_amdgcn_perm(0u, t, 0x0c0c0001u));
-    } else {
-      // c is 0..3: the first two bytes if c >= 2, the last byte if c is odd
-      if (r.cc & (2u << (2 * k))) lds_store16(p, __builtin_amdgcn_perm(0u, t, c == 3 ? 0x0c0c0102u : 0x0c0c0001u));
-      if (r.cc & (1u << (2 * k))) p[c & 2u] = (unsigned char)t;
+  {
+    const u32 q = off + 4u * l8;
+    const u32 sel = __builtin_amdgcn_alignbyte(0x00070605u, 0x04030201u, ~q);     // bytes 4-a, 5-a, 6-a, 7-a
+    u32* w = body32 + (q >> 2);
+    if (FULL || 4u * l8 < r.nlead) {
+      lds_or32(w, __builtin_amdgcn_perm(r.lc, 0u, sel));
+      lds_or32(w + 1, __builtin_amdgcn_perm(0u, r.lc, sel));
     }
-    p += c;
+  }
+  u32 p = off + r.nlead + (r.incl - r.len);
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    u32 a3 = 0, a2 = 0, a1 = 0, a0 = 0, bytes = 0;
+#pragma unroll
+    for (int e = 3; e >= 0; --e) {
+      const int k = 4 * g + e;
+      u32 c = r.nb - ((r.lc >> (2 * k)) & 3u);
+      if (!FULL && k >= r.nv) c = 0;
+      const u32 c1 = c < 2u ? c : 2u, c2 = c - c1;
+      const u32 t = r.t[k], th = t >> (8u * c1);
+      bytes += c;
+      // pushes number 2 (3 - e) + 1 and + 2: the string holds at most 2 (pushes so far) bytes, so the low registers
+      // only take part from the push on that can reach them
+      const int n1 = 2 * (3 - e) + 1, n2 = n1 + 1;
+      if (n1 >= 7) a0 = __builtin_amdgcn_alignbyte(a1, a0, c1);
+      if (n1 >= 5) a1 = __builtin_amdgcn_alignbyte(a2, a1, c1);
+      if (n1 >= 3) a2 = __builtin_amdgcn_alignbyte(a3, a2, c1);
+      a3 = __builtin_amdgcn_alignbyte(t, a3, c1);
+      if (n2 >= 7) a0 = __builtin_amdgcn_alignbyte(a1, a0, c2);
+      if (n2 >= 5) a1 = __builtin_amdgcn_alignbyte(a2, a1, c2);
+      if (n2 >= 3) a2 = __builtin_amdgcn_alignbyte(a3, a2, c2);
+      a3 = __builtin_amdgcn_alignbyte(th, a3, c2);
+    }
+    const u32 sel = __builtin_amdgcn_alignbyte(0x00000102u, 0x03040506u, ~p);    // bytes a+3, a+2, a+1, a with a = p & 3
+    u32* w = body32 + (p >> 2);
+    lds_or32(w, __builtin_amdgcn_perm(0u, a3, sel));
+    lds_or32(w + 1, __builtin_amdgcn_perm(a3, a2, sel));
+    lds_or32(w + 2, __builtin_amdgcn_perm(a2, a1, sel));
+    lds_or32(w + 3, __builtin_amdgcn_perm(a1, a0, sel));
+    lds_or32(w + 4, __builtin_amdgcn_perm(a0, 0u, sel));
+    p += bytes;
   }
 }
 
@@ -1404,7 +1419,7 @@ __device__ __forceinline__ u32 encode_unit(const u32 (&xb)[kE], int nv, int blen
   const UnitPos o = place_unit<FULL, CAP>(r.len, active, blen, blk, nbc, rc, gm, L, bodybase, flushed, slot, src);
   r.incl = o.incl; r.nlead = o.nlead;
   if (active) {
-    if (anyraw) write_body<FULL, true, false>(r, L.body + o.start);
+    if (anyraw) write_body_or4<FULL>(r, (u32*)L.body, o.start);
     else if (__ballot(r.nb != 2u) == 0) write_body_or<FULL, true>(r, (u32*)L.body, o.start);     // active lanes only
     else write_body_or<FULL, false>(r, (u32*)L.body, o.start);
   }
