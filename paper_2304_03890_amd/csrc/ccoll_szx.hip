@@ -1443,11 +1443,9 @@ __device__ __forceinline__ ChunkOut encode_chunk(Src& src, u32 c, const Params& 
   const u32 lane = threadIdx.x & 63u;
   const int nbc = FULL ? kBpc : (int)((P.n - (u64)c * kChunk + kBlock - 1) / kBlock);
   const int nunits = FULL ? kUnits : (nbc + 7) / 8;
-  // the first unit's floats are requested in front of the source's own set-up (the reduce step locates and parses the
-  // incoming chunk there: two memory round trips that this request then shares)
+  src.begin_chunk(c, P, L.body);
   if (!(Src::kPrefetch && preloaded)) src.template load<FULL>(P, c, 0, xa, nv, blen);
   preloaded = false;
-  src.begin_chunk(c, P, L.body);
   u32 bodybase = 0, flushed = 0;
 #pragma unroll 1
   for (int u = 0; u < nunits; ++u) {
@@ -1670,19 +1668,11 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
       if (have) ((u32*)(KARGP(unsigned char*, out) + kHeader))[c] = o.payload;       // the front index entry (Sec. III-E.2)
     }
     __syncthreads();
-    const u32 qnext = (u32)g.nextq[par];
     if (wv == 0) {                                            // announce this group's size
       u32 gtot = 0;
 #pragma unroll
       for (int j = 0; j < NW; ++j) gtot += g.size[ts][j];
       publish_size(KARGP(u64*, stat), q, gtot, KARG32(scan_epoch));
-      if (qnext >= ngroups) {
-        // the workgroup's last group: nothing will be coded behind it, so its place is looked up now, while the other
-        // wavefronts place the group before it (the result is read behind the loop, after a barrier)
-        u64 pb = 0;
-        const bool pr = lookback(KARGP(u64*, stat), q, gtot, P, pb);
-        if (lane == 0) { g.pres[par ^ 1u] = pr ? 1u : 0u; g.pbase[par ^ 1u] = pb; }
-      }
     }
     if (pend) {
       if (g.pres[par] == 0) { dead = true; break; }           // the scan wait was abandoned: error raised, everyone leaves
@@ -1693,10 +1683,18 @@ __device__ __forceinline__ void encode_groups(Src& src, const Params& P, GroupLd
       }
     }
     pend = true; phave = have; pq = q; pc = c; po = o;
-    q = qnext;
+    q = (u32)g.nextq[par];
   }
-  if (pend && !dead) {                                        // the last group of this workgroup is still parked; its place
-    const u32 par = turn & 1u, tp = (turn + 2u) % 3u;         // has been looked up by the first wavefront in the last turn
+  if (pend && !dead) {                                        // the last group of this workgroup is still parked
+    const u32 par = turn & 1u, tp = (turn + 2u) % 3u;
+    if (wv == 0) {
+      u32 ptot = 0;
+#pragma unroll
+      for (int j = 0; j < NW; ++j) ptot += g.size[tp][j];
+      u64 pb = 0;
+      const bool pr = lookback(KARGP(u64*, stat), pq, ptot, P, pb);
+      if (lane == 0) { g.pres[par] = pr ? 1u : 0u; g.pbase[par] = pb; }
+    }
     __syncthreads();
     if (g.pres[par] == 1 && phave) {
       u64 off = g.pbase[par];
