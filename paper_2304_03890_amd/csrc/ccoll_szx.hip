@@ -268,19 +268,27 @@ __device__ __forceinline__ bool lookback(u64* stat, u32 c, u64 mine, const Param
         }
         __builtin_amdgcn_s_sleep(2);
       }
+      // Sizes in front of the nearest full prefix are group sizes (< 2^20 each, at most 256 per round trip): they are
+      // added up in 32 bits, per lane over the four windows and then over the wavefront with one DPP scan; the
+      // prefix itself (36 bits) is read from its lane.
+      u32 part = 0;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         if (!done) {
           const u64 pmask = __ballot((s[q] & kFlagMask) == kFlagP);
-          u64 v = s[q] & kValueMask;
+          const u64 v = s[q] & kValueMask;
           if (pmask) {
             const int first = __ffsll((long long)pmask) - 1;     // nearest predecessor with a full prefix
-            if ((int)lane > first) v = 0;
+            excl += ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(v >> 32), first) << 32) |
+                    (u64)(u32)__builtin_amdgcn_readlane((int)(u32)v, first);
+            if ((int)lane < first) part += (u32)v;
             done = true;
+          } else {
+            part += (u32)v;
           }
-          excl += wave_sum_u64(v);
         }
       }
+      excl += (u64)(u32)__builtin_amdgcn_readlane((int)wave_scan_add(part), 63);
       look -= 256;
     }
     if (lane == 0) st_dev(stat + c, kFlagP | tag | (excl + mine));
